@@ -1,0 +1,117 @@
+/*
+ * ws_synapse.h -- C ABI of the Topological Synapse hot path for AMD MI355X (gfx950).
+ *
+ * The Topological Synapse (Warp-Cortex, Sec. 3.3) is a shared buffer holding k << L
+ * "landmark" rows of the main agent's KV cache; side agents attend over those k rows
+ * instead of the whole context.  Landmarks are chosen per KV head by treating the L
+ * cached keys as a point cloud and scoring each point by a hybrid of geometric
+ * coverage and inverse kernel density (Sec. 3.3, "Hybrid Density-Coverage Sampler";
+ * Sec. 2, first paragraph).  The four entry points below are the four stages of that
+ * path: density -> select -> gather -> attend.
+ *
+ * Conventions shared by every entry point
+ *   - Pointers marked "dev" are device (HBM) pointers; "host" are host pointers.
+ *   - Tensors are dense row-major with the head dimension d innermost.  "H" is
+ *     whatever the caller flattens into independent KV heads (layers x heads).
+ *   - dtype selects the element type of K, V, Q, Ks, Vs: WS_F32 (4 bytes) or WS_BF16
+ *     (2 bytes, upper half of an IEEE float).  Accumulation is always fp32.
+ *   - K, V, Q, Ks, Vs must be 16-byte aligned; d must be 64 or 128.
+ *   - The caller owns every buffer, including the workspace (size from
+ *     ws_synapse_workspace_bytes, 256-byte aligned).  The library allocates nothing,
+ *     keeps no state between calls and never synchronises the host: all work is
+ *     enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream),
+ *     so a caller can run the producer on one stream and the agents on others
+ *     (Sec. 3.1).  Two calls that share a workspace must be ordered by the caller.
+ *   - Errors are return codes only.  Arguments are validated on the host before any
+ *     launch; on an error nothing has been enqueued.  Non-finite inputs give
+ *     undefined results, not errors.
+ */
+#ifndef WS_SYNAPSE_H
+#define WS_SYNAPSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WS_OK = 0,
+    WS_ERR_INVALID_ARG = 1,  /* NULL pointer, size < 1, k > L, alpha outside [0,1], sigma <= 0, misalignment */
+    WS_ERR_UNSUPPORTED = 2,  /* d not in {64,128}, unknown dtype, L >= 2^24 */
+    WS_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or smaller than ws_synapse_workspace_bytes() */
+    WS_ERR_HIP = 4           /* a HIP call or kernel launch failed; see hipGetLastError() */
+} ws_status;
+
+typedef enum { WS_F32 = 0, WS_BF16 = 1 } ws_dtype;
+
+typedef enum { WS_OP_DENSITY = 0, WS_OP_SELECT = 1, WS_OP_GATHER = 2, WS_OP_ATTEND = 3 } ws_op;
+
+typedef void *ws_stream; /* hipStream_t */
+
+/*
+ * Gaussian kernel density of every key against all keys of the same head
+ * (the "inverse kernel density" ingredient of the hybrid score, Sec. 2 and Sec. 3.3):
+ *     rho[h,i] = (1/L) * sum_{j<L} exp(-||K[h,i]-K[h,j]||^2 / (2 sigma[h]^2)),  j = i included,
+ * no Gaussian normalising constant, so 1/L <= rho <= 1.
+ *   K          dev  [H,L,d] keys, dtype `dt`
+ *   sigma_host host [H] bandwidths, each finite and > 0 (read before the call returns)
+ *   rho        dev  [H,L] fp32, written
+ */
+ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d,
+                             const float *sigma_host, float *rho,
+                             void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/*
+ * Greedy landmark choice per head (Sec. 3.3: coverage in the Hausdorff sense balanced
+ * against inverse density; k landmarks).  With u_i = min_j(rho_j)/rho_i, D_i the Euclidean
+ * distance from key i to the nearest landmark chosen so far and D_max the current maximum
+ * of D over the keys not yet chosen, step t picks
+ *     argmax_i  alpha * D_i/D_max + (1-alpha) * u_i      over keys not yet chosen,
+ * lowest index on ties; D_max == 0 makes the first term 0.  With no landmark yet the first
+ * term is 1 for every key, so step 0 picks argmax u (alpha < 1) or index 0 (alpha == 1).
+ *   K         dev [H,L,d];  rho dev [H,L] fp32 (from ws_synapse_density)
+ *   k         landmarks per head, 1 <= k <= L;  alpha in [0,1] (1 = coverage only)
+ *   idx       dev [H,k] int32, written in pick order
+ *   score_out dev [H,k] fp32 winning score per step, or NULL
+ * The kernel is persistent and its workgroups wait on each other with a bounded spin; should
+ * a wait ever expire, the remaining entries of idx for the affected heads are written as -1.
+ */
+ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d,
+                            const float *rho, int k, float alpha,
+                            int32_t *idx, float *score_out,
+                            void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/*
+ * Fill the synapse buffer (Sec. 3.3, "a shared memory buffer containing only Landmarks"):
+ *     Ks[h,t,:] = K[h, idx[h,t], :],  Vs[h,t,:] = V[h, idx[h,t], :]     (bit copies, pick order)
+ *   K, V dev [H,L,d];  idx dev [H,k] with 0 <= idx < L;  Ks, Vs dev [H,k,d], written.
+ * An index outside [0,L) is clamped into range rather than followed.
+ */
+ws_status ws_synapse_gather(const void *K, const void *V, ws_dtype dt, int H, int L, int d,
+                            const int32_t *idx, int k, void *Ks, void *Vs, ws_stream stream);
+
+/*
+ * N agents' decode queries attend over the k landmarks instead of the L-row context
+ * (Sec. 3.3 gives the 1/sqrt(d_k) scale; Sec. 4 states the O(k) cost):
+ *     O[n,q,:] = softmax_t( scale * Q[n,q,:] . Ks[q/g,t,:] ) . Vs[q/g,:,:],   g = Hq/Hkv, t < k
+ * no mask (every landmark is past context); all agents read the same synapse.
+ *   Q dev [N,Hq,d];  Ks, Vs dev [Hkv,k,d];  Hq % Hkv == 0;  scale <= 0 means 1/sqrt(d)
+ *   O dev [N,Hq,d] fp32, written.  workspace may be NULL when the reported size is 0.
+ */
+ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dtype dt,
+                            int N, int Hq, int Hkv, int k, int d, float scale, float *O,
+                            void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/* Bytes of workspace the given operation needs for these sizes (0 if none).  Arguments an
+ * operation does not use are ignored.  Returns (size_t)-1 for unsupported sizes. */
+size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, int k, int N, int Hq);
+
+/* Static, NUL-terminated description of a status code. */
+const char *ws_status_string(ws_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WS_SYNAPSE_H */

@@ -1,0 +1,166 @@
+"""Thin ctypes binding of the C ABI in include/ws_synapse.h.
+
+Same names as the C entry points; argument marshalling only.  PyTorch supplies device
+memory (inputs, outputs, workspace) and the current HIP stream; every step of the path runs
+in the library's kernels.  There is no CPU fallback: if the library has not been built the
+import of a symbol fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+WS_OK, WS_ERR_INVALID_ARG, WS_ERR_UNSUPPORTED, WS_ERR_WORKSPACE, WS_ERR_HIP = range(5)
+WS_F32, WS_BF16 = 0, 1
+WS_OP_DENSITY, WS_OP_SELECT, WS_OP_GATHER, WS_OP_ATTEND = range(4)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libws_synapse.so")
+_lib = None
+
+
+class WsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2601_01298_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci, cf = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+        L.ws_synapse_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci]
+        L.ws_synapse_workspace_bytes.restype = sz
+        L.ws_synapse_density.argtypes = [vp, ci, ci, ci, ci, ctypes.POINTER(cf), vp, vp, sz, vp]
+        L.ws_synapse_density.restype = ci
+        L.ws_synapse_select.argtypes = [vp, ci, ci, ci, ci, vp, ci, cf, vp, vp, vp, sz, vp]
+        L.ws_synapse_select.restype = ci
+        L.ws_synapse_gather.argtypes = [vp, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp]
+        L.ws_synapse_gather.restype = ci
+        L.ws_synapse_attend.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
+        L.ws_synapse_attend.restype = ci
+        L.ws_status_string.argtypes = [ci]
+        L.ws_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ws_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return WS_F32
+    if t.dtype == torch.bfloat16:
+        return WS_BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    return t
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _workspace(nbytes: int, device, workspace):
+    if workspace is None:
+        workspace = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def _check(status: int, where: str):
+    if status != WS_OK:
+        raise WsError(status, where)
+
+
+def ws_synapse_workspace_bytes(op: int, dt: int, H: int, L: int, d: int, k: int = 1, N: int = 1, Hq: int = 1) -> int:
+    n = lib().ws_synapse_workspace_bytes(op, dt, H, L, d, k, N, Hq)
+    if n == ctypes.c_size_t(-1).value:
+        raise WsError(WS_ERR_UNSUPPORTED, "ws_synapse_workspace_bytes")
+    return int(n)
+
+
+def ws_synapse_density(K: torch.Tensor, sigma, rho: torch.Tensor | None = None, workspace=None, stream=None):
+    """K [H,L,d] device; sigma: H host floats -> rho [H,L] fp32 device."""
+    _dev(K, "K")
+    H, L, d = K.shape
+    dt = _dtype_code(K)
+    sig = (ctypes.c_float * H)(*[float(s) for s in sigma])
+    if rho is None:
+        rho = torch.empty((H, L), dtype=torch.float32, device=K.device)
+    need = ws_synapse_workspace_bytes(WS_OP_DENSITY, dt, H, L, d)
+    workspace = _workspace(need, K.device, workspace)
+    _check(lib().ws_synapse_density(K.data_ptr(), dt, H, L, d, sig, _dev(rho, "rho").data_ptr(),
+                                    workspace.data_ptr(), workspace.numel(), _stream(stream)), "ws_synapse_density")
+    return rho
+
+
+def ws_synapse_select(K: torch.Tensor, rho: torch.Tensor, k: int, alpha: float, idx: torch.Tensor | None = None,
+                      score_out: torch.Tensor | None = None, workspace=None, stream=None, want_score: bool = False):
+    """K [H,L,d], rho [H,L] -> idx [H,k] int32 (and the winning scores [H,k] when asked)."""
+    _dev(K, "K")
+    _dev(rho, "rho")
+    H, L, d = K.shape
+    dt = _dtype_code(K)
+    if idx is None:
+        idx = torch.empty((H, k), dtype=torch.int32, device=K.device)
+    if score_out is None and want_score:
+        score_out = torch.empty((H, k), dtype=torch.float32, device=K.device)
+    need = ws_synapse_workspace_bytes(WS_OP_SELECT, dt, H, L, d, k)
+    workspace = _workspace(need, K.device, workspace)
+    _check(lib().ws_synapse_select(K.data_ptr(), dt, H, L, d, rho.data_ptr(), int(k), float(alpha),
+                                   _dev(idx, "idx").data_ptr(),
+                                   score_out.data_ptr() if score_out is not None else None,
+                                   workspace.data_ptr(), workspace.numel(), _stream(stream)), "ws_synapse_select")
+    return (idx, score_out) if (want_score or score_out is not None) else idx
+
+
+def ws_synapse_gather(K: torch.Tensor, V: torch.Tensor, idx: torch.Tensor, Ks: torch.Tensor | None = None,
+                      Vs: torch.Tensor | None = None, stream=None):
+    """K,V [H,L,d], idx [H,k] -> Ks,Vs [H,k,d] (bit copies in pick order)."""
+    _dev(K, "K")
+    _dev(V, "V")
+    _dev(idx, "idx")
+    H, L, d = K.shape
+    k = idx.shape[1]
+    dt = _dtype_code(K)
+    if Ks is None:
+        Ks = torch.empty((H, k, d), dtype=K.dtype, device=K.device)
+    if Vs is None:
+        Vs = torch.empty((H, k, d), dtype=V.dtype, device=K.device)
+    _check(lib().ws_synapse_gather(K.data_ptr(), V.data_ptr(), dt, H, L, d, idx.data_ptr(), k,
+                                   _dev(Ks, "Ks").data_ptr(), _dev(Vs, "Vs").data_ptr(), _stream(stream)),
+           "ws_synapse_gather")
+    return Ks, Vs
+
+
+def ws_synapse_attend(Q: torch.Tensor, Ks: torch.Tensor, Vs: torch.Tensor, scale: float = 0.0,
+                      O: torch.Tensor | None = None, workspace=None, stream=None):
+    """Q [N,Hq,d], Ks,Vs [Hkv,k,d] -> O [N,Hq,d] fp32.  scale <= 0 means 1/sqrt(d)."""
+    _dev(Q, "Q")
+    _dev(Ks, "Ks")
+    _dev(Vs, "Vs")
+    N, Hq, d = Q.shape
+    Hkv, k, _ = Ks.shape
+    dt = _dtype_code(Q)
+    if O is None:
+        O = torch.empty((N, Hq, d), dtype=torch.float32, device=Q.device)
+    wptr, wlen = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(lib().ws_synapse_attend(Q.data_ptr(), Ks.data_ptr(), Vs.data_ptr(), dt, N, Hq, Hkv, k, d, float(scale),
+                                   _dev(O, "O").data_ptr(), wptr, wlen, _stream(stream)), "ws_synapse_attend")
+    return O

@@ -1,0 +1,131 @@
+// C-ABI front end: argument validation on the host, then the kernel launchers.
+// Nothing here allocates, synchronises the host or keeps state between calls.
+#include "../../include/ws_synapse.h"
+
+#include <cmath>
+
+#include "ws_internal.h"
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+ws_status check_common(ws_dtype dt, int d)
+{
+    if (dt != WS_F32 && dt != WS_BF16) return WS_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128) return WS_ERR_UNSUPPORTED;
+    return WS_OK;
+}
+
+ws_status check_ws(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return WS_OK;
+    if (ws == nullptr || !aligned(ws, 256) || have < need) return WS_ERR_WORKSPACE;
+    return WS_OK;
+}
+
+constexpr int kMaxL = 1 << 24;   // candidate indices travel in 24 bits inside the selection kernel
+
+}  // namespace
+
+extern "C" {
+
+size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, int k, int N, int Hq)
+{
+    (void)k;
+    (void)N;
+    (void)Hq;
+    if (check_common(dt, d) != WS_OK) return (size_t)-1;
+    switch (op) {
+    case WS_OP_DENSITY:
+        if (H < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
+        return ws::density_workspace_bytes(H, L);
+    case WS_OP_SELECT:
+        if (H < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
+        return ws::select_workspace_bytes(H, L, d, dt == WS_BF16);
+    case WS_OP_GATHER:
+    case WS_OP_ATTEND:
+        return 0;
+    }
+    return (size_t)-1;
+}
+
+ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d, const float *sigma_host, float *rho,
+                             void *workspace, size_t workspace_bytes, ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!K || !sigma_host || !rho || H < 1 || L < 1) return WS_ERR_INVALID_ARG;
+    if (L >= kMaxL) return WS_ERR_UNSUPPORTED;
+    if (!aligned(K, 16) || !aligned(rho, 4)) return WS_ERR_INVALID_ARG;
+    s = check_ws(workspace, workspace_bytes, ws::density_workspace_bytes(H, L));
+    if (s != WS_OK) return s;
+    for (int h = 0; h < H; ++h) {
+        const double sg = (double)sigma_host[h];
+        const float sc = (float)(1.4426950408889634 / (sg * sg));   // the exponent scale the kernel will use
+        if (!(sg > 0.0) || !std::isfinite(sg) || !std::isfinite(sc) || sc <= 0.0f) return WS_ERR_INVALID_ARG;
+    }
+    const hipError_t e = ws::launch_density(K, dt == WS_BF16, H, L, d, sigma_host, rho, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d, const float *rho, int k, float alpha,
+                            int32_t *idx, float *score_out, void *workspace, size_t workspace_bytes,
+                            ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!K || !rho || !idx || H < 1 || L < 1 || k < 1 || k > L) return WS_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return WS_ERR_INVALID_ARG;
+    if (L >= kMaxL) return WS_ERR_UNSUPPORTED;
+    if (!aligned(K, 16) || !aligned(rho, 4) || !aligned(idx, 4)) return WS_ERR_INVALID_ARG;
+    s = check_ws(workspace, workspace_bytes, ws::select_workspace_bytes(H, L, d, dt == WS_BF16));
+    if (s != WS_OK) return s;
+    const hipError_t e = ws::launch_select(K, dt == WS_BF16, H, L, d, rho, k, alpha, idx, score_out, workspace,
+                                           (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_gather(const void *K, const void *V, ws_dtype dt, int H, int L, int d, const int32_t *idx, int k,
+                            void *Ks, void *Vs, ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!K || !V || !idx || !Ks || !Vs || H < 1 || L < 1 || k < 1) return WS_ERR_INVALID_ARG;
+    if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Ks, 16) || !aligned(Vs, 16) || !aligned(idx, 4))
+        return WS_ERR_INVALID_ARG;
+    const int row_bytes = d * (dt == WS_BF16 ? 2 : 4);
+    const hipError_t e = ws::launch_gather(K, V, row_bytes, H, L, idx, k, Ks, Vs, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dtype dt, int N, int Hq, int Hkv, int k,
+                            int d, float scale, float *O, void *workspace, size_t workspace_bytes, ws_stream stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!Q || !Ks || !Vs || !O || N < 1 || Hq < 1 || Hkv < 1 || k < 1) return WS_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0) return WS_ERR_INVALID_ARG;
+    if (Hkv > 65535) return WS_ERR_UNSUPPORTED;
+    if (!aligned(Q, 16) || !aligned(Ks, 16) || !aligned(Vs, 16) || !aligned(O, 16)) return WS_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return WS_ERR_INVALID_ARG;
+    if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)d);
+    const hipError_t e = ws::launch_attend(Q, Ks, Vs, dt == WS_BF16, N, Hq, Hkv, k, d, scale, O, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+const char *ws_status_string(ws_status s)
+{
+    switch (s) {
+    case WS_OK: return "ok";
+    case WS_ERR_INVALID_ARG: return "invalid argument";
+    case WS_ERR_UNSUPPORTED: return "unsupported size or dtype";
+    case WS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case WS_ERR_HIP: return "HIP runtime or launch failure";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

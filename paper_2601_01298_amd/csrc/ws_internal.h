@@ -1,0 +1,51 @@
+// Internal declarations shared by the kernel files and the C-ABI front end.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ws {
+
+constexpr int kWave = 64;
+
+static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+// ---- density -------------------------------------------------------------------------
+// Keys per head are padded to a multiple of 128 in the per-key side records.
+static inline int density_lpad(int L) { return (int)round_up((size_t)L, 128); }
+size_t density_workspace_bytes(int H, int L);
+// sigma_host[h] > 0 (validated by the caller); enqueues prepass + main sweep.
+hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const float *sigma_host,
+                          float *rho, void *ws, hipStream_t st);
+
+// ---- selection -----------------------------------------------------------------------
+struct SelectPlan {
+    int groups;   // heads processed concurrently (each by `members` workgroups)
+    int members;  // workgroups cooperating on one head
+    int threads;  // threads per workgroup
+};
+SelectPlan select_plan(int H, int L, int d, bool bf16);
+size_t select_workspace_bytes(int H, int L, int d, bool bf16);
+hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
+                         float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st);
+
+// ---- gather --------------------------------------------------------------------------
+hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int L,
+                         const int32_t *idx, int k, void *Ks, void *Vs, hipStream_t st);
+
+// ---- attention -----------------------------------------------------------------------
+hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq,
+                         int Hkv, int k, int d, float scale, float *O, hipStream_t st);
+
+// Workgroup ids are handed to the 8 accelerator dies (XCDs) round-robin, and each die has
+// its own L2.  This maps a hardware workgroup id to a logical id so that each die works on
+// one contiguous range of logical ids (neighbouring tiles of the same head share an L2).
+__device__ __forceinline__ int xcd_contiguous(int b, int total)
+{
+    const int xcd = b & 7, j = b >> 3;
+    const int per = total >> 3, rem = total & 7;
+    const int start = (xcd < rem) ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+    return start + j;
+}
+
+}  // namespace ws

@@ -1,0 +1,94 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ws_synapse.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2601_01298_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ws_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert {"ws_synapse_density", "ws_synapse_select", "ws_synapse_gather", "ws_synapse_attend",
+            "ws_synapse_workspace_bytes", "ws_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_has_the_same_names():
+    from paper_2601_01298_amd import binding
+    for n in declared_symbols():
+        if n.startswith("ws_synapse_"):
+            assert callable(getattr(binding, n)), n
+
+
+def test_status_strings(lib):
+    from paper_2601_01298_amd import binding
+    seen = {binding.status_string(s) for s in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+
+
+def test_workspace_query(lib):
+    from paper_2601_01298_amd import binding as b
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_GATHER, b.WS_BF16, 4, 100, 64) == 0
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTEND, b.WS_BF16, 4, 100, 64) == 0
+    n1 = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 4, 1000, 64)
+    n2 = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 8, 1000, 64)
+    assert 0 < n1 < n2 and n1 >= 4 * 1000 * 16
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_SELECT, b.WS_F32, 1, 512, 64) > 0
+    with pytest.raises(b.WsError):
+        b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 4, 1000, 96)      # d not in {64,128}
+    with pytest.raises(b.WsError):
+        b.ws_synapse_workspace_bytes(b.WS_OP_SELECT, b.WS_BF16, 4, 1 << 24, 64)    # L too large
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    from paper_2601_01298_amd import binding as b
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)            # aligned, never dereferenced: validation fails first
+    odd = vp(0x1004)
+    sig = (ctypes.c_float * 2)(1.0, 1.0)
+    bad_sig = (ctypes.c_float * 2)(1.0, 0.0)
+    nan_sig = (ctypes.c_float * 2)(1.0, float("nan"))
+    D = lib.ws_synapse_density
+    assert D(None, b.WS_BF16, 2, 100, 64, sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert D(fake, b.WS_BF16, 2, 100, 96, sig, fake, fake, 1 << 30, None) == b.WS_ERR_UNSUPPORTED
+    assert D(fake, 7, 2, 100, 64, sig, fake, fake, 1 << 30, None) == b.WS_ERR_UNSUPPORTED
+    assert D(fake, b.WS_BF16, 0, 100, 64, sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert D(odd, b.WS_BF16, 2, 100, 64, sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert D(fake, b.WS_BF16, 2, 100, 64, sig, fake, None, 0, None) == b.WS_ERR_WORKSPACE
+    assert D(fake, b.WS_BF16, 2, 100, 64, sig, fake, fake, 16, None) == b.WS_ERR_WORKSPACE
+    assert D(fake, b.WS_BF16, 2, 100, 64, bad_sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert D(fake, b.WS_BF16, 2, 100, 64, nan_sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    S = lib.ws_synapse_select
+    assert S(fake, b.WS_BF16, 2, 100, 64, fake, 101, 0.5, fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert S(fake, b.WS_BF16, 2, 100, 64, fake, 0, 0.5, fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, 1.5, fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, float("nan"), fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, None, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, fake, None, fake, 8, None) == b.WS_ERR_WORKSPACE
+    G = lib.ws_synapse_gather
+    assert G(fake, None, b.WS_BF16, 2, 100, 64, fake, 10, fake, fake, None) == b.WS_ERR_INVALID_ARG
+    assert G(fake, fake, b.WS_BF16, 2, 100, 32, fake, 10, fake, fake, None) == b.WS_ERR_UNSUPPORTED
+    A = lib.ws_synapse_attend
+    assert A(fake, fake, fake, b.WS_BF16, 4, 6, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG   # 6 % 4
+    assert A(fake, fake, fake, b.WS_BF16, 0, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
+    assert A(fake, fake, fake, b.WS_BF16, 4, 4, 4, 10, 64, float("inf"), fake, None, 0, None) == b.WS_ERR_INVALID_ARG
+    assert A(fake, fake, None, b.WS_BF16, 4, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
