@@ -75,8 +75,12 @@ ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d,
  *   k         landmarks per head, 1 <= k <= L;  alpha in [0,1] (1 = coverage only)
  *   idx       dev [H,k] int32, written in pick order
  *   score_out dev [H,k] fp32 winning score per step, or NULL
- * The kernel is persistent and its workgroups wait on each other with a bounded spin; should
- * a wait ever expire, the remaining entries of idx for the affected heads are written as -1.
+ * Two kernels implement this call: one keeps a head's keys resident in registers and LDS for all
+ * k steps (bf16 keys, heads that fit on chip), one streams them from memory every step (any size).
+ * The library picks; the environment variable WS_SYNAPSE_SELECT=stream|resident forces one
+ * (resident fails with WS_ERR_HIP when the sizes do not fit).  Both are persistent and their waves
+ * wait on each other with a bounded spin; should a wait ever expire, the remaining entries of idx
+ * for the affected heads are written as -1.
  */
 ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d,
                             const float *rho, int k, float alpha,

@@ -16,6 +16,8 @@
 // memory.  Every word carries an 8-bit sequence tag, slots are double-buffered by exchange
 // parity, and every wait is bounded: if it expires the group flags the failure, writes -1 into
 // the index entries it still owes and leaves, so the grid always drains.
+#include <cstdlib>
+
 #include "ws_internal.h"
 
 namespace ws {
@@ -319,7 +321,13 @@ SelectPlan select_plan(int H, int L, int d, bool bf16)
 
 size_t select_workspace_bytes(int H, int L, int d, bool bf16)
 {
-    return layout(select_plan(H, L, d, bf16), L).total;
+    // large enough for either kernel, so the choice can be made (or forced) at call time
+    size_t n = layout(select_plan(H, L, d, bf16), L).total;
+    if (resident_select_supported(H, L, d, bf16)) {
+        const size_t r = resident_select_workspace_bytes(H, L, d);
+        if (r > n) n = r;
+    }
+    return n;
 }
 
 template <typename T, int D>
@@ -332,6 +340,15 @@ static hipError_t run_select(const SelArgs &a, const SelectPlan &p, hipStream_t 
 hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k, float alpha,
                          int32_t *idx, float *score_out, void *ws, hipStream_t st)
 {
+    // Keys that fit on chip are selected by the resident kernel; the environment variable
+    // WS_SYNAPSE_SELECT=stream|resident overrides the choice (testing, profiling).
+    const char *force = getenv("WS_SYNAPSE_SELECT");
+    const bool can_res = resident_select_supported(H, L, d, bf16);
+    bool use_res = can_res;
+    if (force && force[0] == 's') use_res = false;
+    if (force && force[0] == 'r' && !can_res) return hipErrorInvalidValue;
+    if (use_res) return launch_select_resident(K, H, L, d, rho, k, alpha, idx, score_out, ws, st);
+
     const SelectPlan p = select_plan(H, L, d, bf16);
     const WsLayout w = layout(p, L);
     char *base = reinterpret_cast<char *>(ws);

@@ -1,0 +1,385 @@
+// Greedy landmark selection, register-resident variant (bf16 keys).
+//
+// The selection makes k dependent sweeps over the same L keys of a head (Warp-Cortex Sec. 3.3:
+// one landmark per step, each step needs every key's distance to the landmark just chosen).
+// Streaming those keys from HBM k times costs k*L*d*2 bytes per head; but the register files
+// and LDS of the chip together hold ~100 MB, so a few dozen heads at a time fit ON CHIP.  Here
+// every wave owns 64*R keys for the whole life of a head: lane l keeps R complete key rows
+// (RREG of them in VGPRs, RLDS in a private strip of LDS), its D and u values, and never
+// touches HBM again until the next head.  The landmark row is fetched once per step through
+// the scalar cache into SGPRs and used as a broadcast operand.
+//
+// A head is shared by nw = 4 * (workgroups per head) waves, placed on one accelerator die.
+// Waves, not workgroups, are the unit of cooperation: there is no barrier anywhere in the step
+// loop.  Twice per step every wave posts one tagged 64-bit word (its local D_max, then its local
+// best candidate) into a slot array in global memory and polls the nw slots of its head, one
+// slot per lane; the reduction over the polled words is done with DPP row operations.  Waits are
+// bounded; a wave whose wait expires raises the failure flag, and (if it is the head's writer)
+// writes -1 into the index entries still owed, then leaves.
+#include "ws_internal.h"
+
+namespace ws {
+
+namespace {
+
+constexpr int kMaxWaves = 128;              // waves cooperating on one head (two polls per lane)
+constexpr unsigned kSpinLimit = 1u << 22;
+
+struct ResArgs {
+    const uint16_t *K;
+    const float *rho;
+    int32_t *idx;
+    float *score_out;
+    unsigned long long *slots;   // [groups][2][kMaxWaves]
+    int *fail;
+    int H, L, k;
+    int groups, wgpg;            // heads in flight, workgroups per head
+    float alpha;
+};
+
+// ---- wave-wide unsigned max via DPP: 4 in-row steps, then one lane of each 16-lane row ------
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_umax(unsigned v)
+{
+    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+    return o > v ? o : v;
+}
+
+__device__ __forceinline__ unsigned wave_umax(unsigned v)
+{
+    v = dpp_umax<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_umax<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_umax<0x141>(v);   // row_half_mirror
+    v = dpp_umax<0x140>(v);   // row_mirror
+    const unsigned a = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
+    const unsigned b = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned c = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
+    const unsigned d = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    const unsigned ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+// Post `mine` (low 8 bits zero) for this wave, wait for all nw waves of the head, return the
+// maximum word (as hi/lo halves, tag stripped).  Returns false if the bounded wait expired.
+__device__ __forceinline__ bool exchange_max(unsigned long long mine, unsigned long long *gslots, int nw, int wv,
+                                             unsigned &seq, int lane, unsigned &hi_out, unsigned &lo_out)
+{
+    ++seq;
+    const unsigned tag = seq % 255u + 1u;
+    unsigned long long *slot = gslots + (seq & 1u) * kMaxWaves;
+    if (lane == 0) __hip_atomic_store(slot + wv, mine | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool ok0 = lane >= nw, ok1 = lane + 64 >= nw;
+    unsigned long long g0 = 0ull, g1 = 0ull;
+    unsigned spins = 0;
+    while (true) {
+        if (!ok0) {
+            g0 = __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok0 = (unsigned)(g0 & 0xFFull) == tag;
+        }
+        if (!ok1) {
+            g1 = __hip_atomic_load(slot + lane + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok1 = (unsigned)(g1 & 0xFFull) == tag;
+        }
+        if (__all(ok0 && ok1)) break;
+        if (++spins > kSpinLimit) return false;
+        if (spins > 32) __builtin_amdgcn_s_sleep(2);
+    }
+    if (lane >= nw) g0 = 0ull;
+    if (lane + 64 >= nw) g1 = 0ull;
+    const unsigned long long g = g0 > g1 ? g0 : g1;
+    const unsigned hi = (unsigned)(g >> 32), lo = (unsigned)g & 0xFFFFFF00u;
+    const unsigned mhi = wave_umax(hi);
+    const unsigned mlo = wave_umax(hi == mhi ? lo : 0u);
+    hi_out = mhi;
+    lo_out = mlo;
+    return true;
+}
+
+template <int D, int RREG, int RLDS>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+select_resident(ResArgs a)
+{
+    constexpr int R = RREG + RLDS;
+    constexpr int DW = D / 2;      // 32-bit words per key row
+    constexpr int NV = DW / 4;     // 16-byte pieces per key row
+    __shared__ uint4 lrows[RLDS > 0 ? RLDS * NV * 256 : 1];
+
+    int group, member;
+    if ((a.groups & 7) == 0) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        group = xcd * (a.groups >> 3) + j / a.wgpg;
+        member = j % a.wgpg;
+    } else {
+        group = blockIdx.x / a.wgpg;
+        member = blockIdx.x % a.wgpg;
+    }
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = member * 4 + (tid >> 6);
+    const int nw = a.wgpg * 4;
+    const int rowbase = wv * (R * 64) + lane;          // this lane's r-th key is rowbase + 64 r
+    unsigned long long *gslots = a.slots + (size_t)group * 2 * kMaxWaves;
+    const float alpha = a.alpha, oma = 1.0f - a.alpha;
+    const float ninf = -__builtin_inff();
+    unsigned seq = 0;
+
+    for (int h = group; h < a.H; h += a.groups) {
+        const uint16_t *Kh = a.K + (size_t)h * a.L * D;
+        const float *rhoh = a.rho + (size_t)h * a.L;
+        int t = 0;
+
+        // ---- bring this lane's keys on chip, once per head
+        uint32_t kr[RREG > 0 ? RREG : 1][DW];
+#pragma unroll
+        for (int r = 0; r < RREG; ++r) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(Kh + (size_t)min(rowbase + 64 * r, a.L - 1) * D);
+#pragma unroll
+            for (int c = 0; c < NV; ++c) {
+                const uint4 q = p[c];
+                kr[r][4 * c] = q.x;
+                kr[r][4 * c + 1] = q.y;
+                kr[r][4 * c + 2] = q.z;
+                kr[r][4 * c + 3] = q.w;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RLDS; ++r) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(Kh + (size_t)min(rowbase + 64 * (RREG + r), a.L - 1) * D);
+#pragma unroll
+            for (int c = 0; c < NV; ++c) lrows[(r * NV + c) * 256 + tid] = p[c];   // private to this thread
+        }
+
+        // ---- u_i = rho_min / rho_i ; keys past L count as already chosen
+        float Dv[R], ou[R];
+        float rmin = __builtin_inff();
+        float rh[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int row = rowbase + 64 * r;
+            rh[r] = rhoh[min(row, a.L - 1)];
+            if (row < a.L) rmin = fminf(rmin, rh[r]);
+        }
+        {
+            unsigned mhi, mlo;
+            const unsigned mine = wave_umax(0xFFFFFFFFu - __float_as_uint(rmin));
+            if (!exchange_max((unsigned long long)mine << 32, gslots, nw, wv, seq, lane, mhi, mlo)) goto bail;
+            rmin = __uint_as_float(0xFFFFFFFFu - mhi);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool live = rowbase + 64 * r < a.L;
+            Dv[r] = live ? __builtin_inff() : -1.0f;
+            ou[r] = live ? oma * (rmin / rh[r]) : ninf;
+        }
+
+        {
+            int prev = 0;
+            for (t = 0; t < a.k; ++t) {
+                float ainv = alpha;          // step 0: coverage term is 1 for every key
+                if (t > 0) {
+                    // ---- distance of every resident key to landmark `prev`
+                    float acc[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) acc[r] = 0.0f;
+                    // The landmark row is the same for every lane: read it through the constant address
+                    // space (K is never written while the kernel runs) so it arrives by scalar loads in
+                    // SGPRs and serves as a broadcast operand instead of occupying 64 VGPRs.
+                    typedef const uint32_t __attribute__((address_space(4))) *cptr_t;
+                    const cptr_t lp = (cptr_t)(uintptr_t)(Kh + (size_t)prev * D);
+                    // The keys sit in registers as packed bf16 pairs and are widened on the fly each
+                    // step.  Shift count and mask go through an empty asm so the compiler cannot treat
+                    // the widened values as loop-invariant and keep a second, twice as large copy.
+                    unsigned sh16 = 16u, mhi16 = 0xFFFF0000u;
+                    asm volatile("" : "+s"(sh16), "+s"(mhi16));
+#pragma unroll
+                    for (int c = 0; c < NV; ++c) {
+                        float lm[8];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t wd = lp[4 * c + j];
+                            lm[2 * j] = __uint_as_float(wd << 16);
+                            lm[2 * j + 1] = __uint_as_float(wd & 0xFFFF0000u);
+                        }
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            uint32_t w4[4];
+                            if (r < RREG) {
+                                w4[0] = kr[r < RREG ? r : 0][4 * c];
+                                w4[1] = kr[r < RREG ? r : 0][4 * c + 1];
+                                w4[2] = kr[r < RREG ? r : 0][4 * c + 2];
+                                w4[3] = kr[r < RREG ? r : 0][4 * c + 3];
+                            } else {
+                                const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
+                                w4[0] = q.x;
+                                w4[1] = q.y;
+                                w4[2] = q.z;
+                                w4[3] = q.w;
+                            }
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const float d0 = __uint_as_float(w4[j] << sh16) - lm[2 * j];
+                                acc[r] = fmaf(d0, d0, acc[r]);
+                                const float d1 = __uint_as_float(w4[j] & mhi16) - lm[2 * j + 1];
+                                acc[r] = fmaf(d1, d1, acc[r]);
+                            }
+                        }
+                    }
+                    float lmax = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        Dv[r] = fminf(Dv[r], __fsqrt_rn(acc[r]));    // chosen keys stay at -1
+                        lmax = fmaxf(lmax, Dv[r]);
+                    }
+                    unsigned mhi, mlo;
+                    const unsigned mine = wave_umax(__float_as_uint(lmax));
+                    if (!exchange_max((unsigned long long)mine << 32, gslots, nw, wv, seq, lane, mhi, mlo)) goto bail;
+                    const float dmax = __uint_as_float(mhi);
+                    ainv = dmax > 0.0f ? alpha / dmax : 0.0f;
+                }
+
+                int s;
+                float sc;
+                if (t == 0 && alpha == 1.0f) {
+                    s = 0;
+                    sc = alpha;
+                } else {
+                    // ---- score = alpha * D/D_max + (1-alpha) * u ; keys in ascending order per lane
+                    float best = -1.0f;
+                    int bi = 0;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const float dd = (t == 0) ? 1.0f : Dv[r];
+                        const float v = fmaf(ainv, dd, ou[r]);
+                        if (v > best) {
+                            best = v;
+                            bi = rowbase + 64 * r;
+                        }
+                    }
+                    const unsigned chi = best >= 0.0f ? __float_as_uint(best) : 0u;
+                    const unsigned clo = best >= 0.0f ? (0xFFFFFFu - (unsigned)bi) << 8 : 0u;
+                    const unsigned whi = wave_umax(chi);
+                    const unsigned wlo = wave_umax(chi == whi ? clo : 0u);
+                    unsigned mhi, mlo;
+                    if (!exchange_max(((unsigned long long)whi << 32) | wlo, gslots, nw, wv, seq, lane, mhi, mlo))
+                        goto bail;
+                    s = (int)(0xFFFFFFu - (mlo >> 8));
+                    sc = __uint_as_float(mhi);
+                }
+                s = __builtin_amdgcn_readfirstlane(s);
+                if (wv == 0 && lane == 0) {
+                    a.idx[(size_t)h * a.k + t] = s;
+                    if (a.score_out) a.score_out[(size_t)h * a.k + t] = sc;
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    if (rowbase + 64 * r == s) {       // chosen: never scored again
+                        Dv[r] = -1.0f;
+                        ou[r] = ninf;
+                    }
+                prev = s;
+            }
+        }
+        continue;
+    bail:
+        if (lane == 0) atomicExch(a.fail, 1);
+        if (wv == 0) {
+            for (int hh = h; hh < a.H; hh += a.groups) {
+                const int t0 = (hh == h) ? t : 0;
+                for (int tt = t0 + lane; tt < a.k; tt += 64) a.idx[(size_t)hh * a.k + tt] = -1;
+            }
+        }
+        return;
+    }
+}
+
+__global__ void resident_clear(unsigned long long *slots, int n, int *fail)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) slots[i] = 0ull;
+    if (i == 0) *fail = 0;
+}
+
+struct Shape {
+    int rreg, rlds, wgpg, groups, rounds;
+};
+
+// Pick rows per lane and workgroups per head: fewest rounds over the heads, then fewest rows per
+// lane (more waves per head, less serial work per step).  512 workgroups of 256 threads are
+// co-resident (2 per compute unit at 256 VGPRs and <= 64 KB LDS each).
+bool pick_shape(int H, int L, int d, Shape &best)
+{
+    static const int opts64[][2] = {{1, 0}, {2, 0}, {4, 0}, {6, 2}};
+    static const int opts128[][2] = {{1, 0}, {2, 0}, {3, 1}};
+    const int(*opts)[2] = d == 64 ? opts64 : opts128;
+    const int nopts = d == 64 ? 4 : 3;
+    bool found = false;
+    for (int i = 0; i < nopts; ++i) {
+        const int R = opts[i][0] + opts[i][1];
+        const int wgpg = (L + 256 * R - 1) / (256 * R);
+        if (wgpg * 4 > kMaxWaves) continue;
+        int groups = 512 / wgpg;
+        if (groups > H) groups = H;
+        if (groups >= 8) groups -= groups % 8;
+        const int rounds = (H + groups - 1) / groups;
+        if (!found || rounds < best.rounds) {
+            best = Shape{opts[i][0], opts[i][1], wgpg, groups, rounds};
+            found = true;
+        }
+    }
+    return found;
+}
+
+template <int D, int RREG, int RLDS>
+hipError_t run(const ResArgs &a, hipStream_t st)
+{
+    hipLaunchKernelGGL((select_resident<D, RREG, RLDS>), dim3(a.groups * a.wgpg), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool resident_select_supported(int H, int L, int d, bool bf16)
+{
+    Shape s;
+    return bf16 && (d == 64 || d == 128) && pick_shape(H, L, d, s);
+}
+
+size_t resident_select_workspace_bytes(int H, int L, int d)
+{
+    Shape s;
+    if (!pick_shape(H, L, d, s)) return 0;
+    return round_up((size_t)s.groups * 2 * kMaxWaves * sizeof(unsigned long long), 256) + 256;
+}
+
+hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
+                                  int32_t *idx, float *score_out, void *ws, hipStream_t st)
+{
+    Shape s;
+    if (!pick_shape(H, L, d, s)) return hipErrorInvalidValue;
+    ResArgs a;
+    a.K = reinterpret_cast<const uint16_t *>(K);
+    a.rho = rho;
+    a.idx = idx;
+    a.score_out = score_out;
+    a.slots = reinterpret_cast<unsigned long long *>(ws);
+    const size_t nslots = (size_t)s.groups * 2 * kMaxWaves;
+    a.fail = reinterpret_cast<int *>(reinterpret_cast<char *>(ws) + round_up(nslots * sizeof(unsigned long long), 256));
+    a.H = H;
+    a.L = L;
+    a.k = k;
+    a.groups = s.groups;
+    a.wgpg = s.wgpg;
+    a.alpha = alpha;
+    hipLaunchKernelGGL(resident_clear, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, st, a.slots, (int)nslots,
+                       a.fail);
+    if (d == 64) {
+        if (s.rreg == 1) return run<64, 1, 0>(a, st);
+        if (s.rreg == 2) return run<64, 2, 0>(a, st);
+        if (s.rreg == 4) return run<64, 4, 0>(a, st);
+        return run<64, 6, 2>(a, st);
+    }
+    if (s.rreg == 1) return run<128, 1, 0>(a, st);
+    if (s.rreg == 2) return run<128, 2, 0>(a, st);
+    return run<128, 3, 1>(a, st);
+}
+
+}  // namespace ws

@@ -29,6 +29,12 @@ size_t select_workspace_bytes(int H, int L, int d, bool bf16);
 hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
                          float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st);
 
+// register/LDS-resident variant (bf16, heads small enough to sit on chip)
+bool resident_select_supported(int H, int L, int d, bool bf16);
+size_t resident_select_workspace_bytes(int H, int L, int d);
+hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
+                                  int32_t *idx, float *score_out, void *ws, hipStream_t st);
+
 // ---- gather --------------------------------------------------------------------------
 hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int L,
                          const int32_t *idx, int k, void *Ks, void *Vs, hipStream_t st);

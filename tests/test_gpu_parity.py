@@ -37,6 +37,17 @@ def variant(cfg, **kw):
     return syn.small_variant(syn.WORKLOADS[cfg], **kw)
 
 
+@pytest.fixture(params=["resident", "stream"])
+def select_kernel(request, monkeypatch):
+    """Run a selection test once per kernel (the library reads the variable at every call;
+    fp32 keys and oversized heads always take the streaming kernel)."""
+    if request.param == "stream":
+        monkeypatch.setenv("WS_SYNAPSE_SELECT", "stream")
+    else:
+        monkeypatch.delenv("WS_SYNAPSE_SELECT", raising=False)
+    return request.param
+
+
 # ------------------------------------------------------------------------------- density
 @pytest.mark.parametrize("cfg,H,L", [(1, 1, 512), (1, 2, 333), (2, 3, 4096), (2, 2, 1000), (2, 1, 31),
                                      (4, 2, 1500), (3, 2, 2048)])
@@ -70,7 +81,7 @@ def test_density_fp32_d128_and_sigma_extremes(ws, oracle):
 
 # ------------------------------------------------------------------------------ selection
 @pytest.mark.parametrize("alpha", [0.0, 0.25, 0.5, 1.0])
-def test_select_tiny_config_all_alphas(ws, oracle, alpha):
+def test_select_tiny_config_all_alphas(ws, oracle, alpha, select_kernel):
     w = syn.WORKLOADS[1]
     head, rejected = accepted_head(oracle, w, 0, alpha)
     K = to_device(head["K"][None], w.dtype)
@@ -83,7 +94,7 @@ def test_select_tiny_config_all_alphas(ws, oracle, alpha):
 
 @pytest.mark.parametrize("cfg,H,L,k", [(2, 16, 4096, 82), (2, 3, 1000, 37), (1, 2, 333, 20), (2, 40, 512, 10),
                                        (3, 2, 8192, 164)])
-def test_select_matches_oracle(ws, oracle, cfg, H, L, k):
+def test_select_matches_oracle(ws, oracle, cfg, H, L, k, select_kernel):
     w = variant(cfg, H=H, L=L, k=k)
     heads, rejected = [], 0
     for h in range(H):
@@ -104,7 +115,7 @@ def test_select_matches_oracle(ws, oracle, cfg, H, L, k):
 
 
 @pytest.mark.parametrize("cfg,H,L,k", [(4, 5, 2048, 41), (5, 3, 4096, 82), (3, 3, 16384, 328)])
-def test_select_with_near_tie_forks(ws, oracle, cfg, H, L, k):
+def test_select_with_near_tie_forks(ws, oracle, cfg, H, L, k, select_kernel):
     """Workloads whose oracle chain cannot be tie-free (uniform outliers all have density exactly
     1/L; long chains): step-granular protocol -- equal, or every differing pick is a <= 1e-5
     near-tie of the oracle's own scores under the GPU's prefix."""
@@ -122,7 +133,7 @@ def test_select_with_near_tie_forks(ws, oracle, cfg, H, L, k):
         print(f"cfg{cfg} head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
 
 
-def test_select_edge_cases(ws, oracle):
+def test_select_edge_cases(ws, oracle, select_kernel):
     import torch
     # k = L on a small cloud: a permutation, and the zero-radius tail of duplicates
     rng = np.random.default_rng(9)
