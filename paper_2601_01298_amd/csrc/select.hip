@@ -245,7 +245,7 @@ select_stream(SelArgs a)
                     }
                     best = group_max<TPB>(best, sh, a, group, member, seq);
                     if (sh.abort) goto bail;
-                    s = (int)(0xFFFFFFu - (unsigned)((best >> 8) & 0xFFFFFFull));
+                    s = min((int)(0xFFFFFFu - (unsigned)((best >> 8) & 0xFFFFFFull)), a.L - 1);   // in range whatever the inputs held
                     sc = __uint_as_float((unsigned)(best >> 32));
                 }
                 if (member == 0 && threadIdx.x == 0) {

@@ -9,20 +9,21 @@
 // touches HBM again until the next head.  The landmark row is fetched once per step through
 // the scalar cache into SGPRs and used as a broadcast operand.
 //
-// A head is shared by nw = 4 * (workgroups per head) waves, placed on one accelerator die.
-// Waves, not workgroups, are the unit of cooperation: there is no barrier anywhere in the step
-// loop.  Twice per step every wave posts one tagged 64-bit word (its local D_max, then its local
-// best candidate) into a slot array in global memory and polls the nw slots of its head, one
-// slot per lane; the reduction over the polled words is done with DPP row operations.  Waits are
-// bounded; a wave whose wait expires raises the failure flag, and (if it is the head's writer)
-// writes -1 into the index entries still owed, then leaves.
+// A head is shared by up to 32 workgroups of 4 waves, placed on one accelerator die.  Twice per
+// step the head needs a maximum over all its keys (D_max, then the best candidate).  Each is
+// reduced in three levels: lanes of a wave with DPP row operations, the waves of a workgroup
+// through LDS, and the workgroups of the head through one tagged 64-bit slot each in global
+// memory, posted and polled by a single wave per workgroup (keeping the number of requests that
+// hit the slots' L2 channel small matters more than saving a barrier).  Waits are bounded; a
+// workgroup whose wait expires raises the failure flag, and (if it is the head's writer) writes -1
+// into the index entries still owed, then leaves.
 #include "ws_internal.h"
 
 namespace ws {
 
 namespace {
 
-constexpr int kMaxWaves = 128;              // waves cooperating on one head (two polls per lane)
+constexpr int kMaxMembers = 32;             // workgroups cooperating on one head
 constexpr unsigned kSpinLimit = 1u << 22;
 
 struct ResArgs {
@@ -30,7 +31,7 @@ struct ResArgs {
     const float *rho;
     int32_t *idx;
     float *score_out;
-    unsigned long long *slots;   // [groups][2][kMaxWaves]
+    unsigned long long *slots;   // [groups][2][kMaxMembers]
     int *fail;
     int H, L, k;
     int groups, wgpg;            // heads in flight, workgroups per head
@@ -59,40 +60,79 @@ __device__ __forceinline__ unsigned wave_umax(unsigned v)
     return ab > cd ? ab : cd;
 }
 
-// Post `mine` (low 8 bits zero) for this wave, wait for all nw waves of the head, return the
-// maximum word (as hi/lo halves, tag stripped).  Returns false if the bounded wait expired.
-__device__ __forceinline__ bool exchange_max(unsigned long long mine, unsigned long long *gslots, int nw, int wv,
-                                             unsigned &seq, int lane, unsigned &hi_out, unsigned &lo_out)
+struct Shared {
+    unsigned hi[4], lo[4];     // one (hi, lo) pair per wave of the workgroup
+    unsigned rhi, rlo;         // result of the exchange
+    int abort;
+};
+
+// Maximum of a (hi, lo) pair -- compared as one 64-bit number, lo has its low 8 bits clear --
+// over every wave of the head.  Three levels: lanes of a wave (done by the caller, `hi`/`lo` are
+// wave-uniform), the 4 waves of a workgroup through LDS, the workgroups of the head through one
+// tagged 64-bit slot each in global memory.  Only wave 0 of a workgroup touches the slots, and
+// only with `nwg` lanes, so a poll round of a whole head costs nwg*nwg small requests at the L2
+// instead of (4 nwg)^2 * 16.  `pf`, if not null, is the key row of this workgroup's candidate:
+// wave 0 touches it after posting, so that it is in this die's L2 when the winner is fetched.
+// Returns false (for every thread of the workgroup) if the bounded wait expired.
+__device__ __forceinline__ bool head_max(unsigned hi, unsigned lo, Shared &sh, unsigned long long *gslots, int nwg,
+                                         int member, unsigned &seq, unsigned &hi_out, unsigned &lo_out,
+                                         const uint16_t *pf_base, int D, int last_row, bool prefetch)
 {
-    ++seq;
-    const unsigned tag = seq % 255u + 1u;
-    unsigned long long *slot = gslots + (seq & 1u) * kMaxWaves;
-    if (lane == 0) __hip_atomic_store(slot + wv, mine | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    bool ok0 = lane >= nw, ok1 = lane + 64 >= nw;
-    unsigned long long g0 = 0ull, g1 = 0ull;
-    unsigned spins = 0;
-    while (true) {
-        if (!ok0) {
-            g0 = __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok0 = (unsigned)(g0 & 0xFFull) == tag;
-        }
-        if (!ok1) {
-            g1 = __hip_atomic_load(slot + lane + 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ok1 = (unsigned)(g1 & 0xFFull) == tag;
-        }
-        if (__all(ok0 && ok1)) break;
-        if (++spins > kSpinLimit) return false;
-        if (spins > 32) __builtin_amdgcn_s_sleep(2);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        sh.hi[wave] = hi;
+        sh.lo[wave] = lo;
     }
-    if (lane >= nw) g0 = 0ull;
-    if (lane + 64 >= nw) g1 = 0ull;
-    const unsigned long long g = g0 > g1 ? g0 : g1;
-    const unsigned hi = (unsigned)(g >> 32), lo = (unsigned)g & 0xFFFFFF00u;
-    const unsigned mhi = wave_umax(hi);
-    const unsigned mlo = wave_umax(hi == mhi ? lo : 0u);
-    hi_out = mhi;
-    lo_out = mlo;
-    return true;
+    __syncthreads();
+    if (wave == 0) {
+        const unsigned h4 = lane < 4 ? sh.hi[lane] : 0u, l4 = lane < 4 ? sh.lo[lane] : 0u;
+        unsigned mh = wave_umax(h4);
+        unsigned ml = wave_umax(h4 == mh ? l4 : 0u);
+        bool good = true;
+        if (nwg > 1) {
+            ++seq;
+            const unsigned tag = seq % 255u + 1u;
+            unsigned long long *slot = gslots + (seq & 1u) * kMaxMembers;
+            if (lane == 0)
+                __hip_atomic_store(slot + member, ((unsigned long long)mh << 32) | ml | tag, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            unsigned touched = 0u;
+            if (prefetch && lane < D / 8) {
+                // candidate index travels in bits 8..31 of lo, complemented
+                const int cand = min((int)(0xFFFFFFu - (ml >> 8)), last_row);
+                touched = *reinterpret_cast<const volatile unsigned *>(pf_base + (size_t)cand * D + lane * 8);
+            }
+            bool ok = lane >= nwg;
+            unsigned long long g = 0ull;
+            unsigned spins = 0;
+            while (true) {
+                if (!ok) {
+                    g = __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = (unsigned)(g & 0xFFull) == tag;
+                }
+                if (__all(ok)) break;
+                if (++spins > kSpinLimit) {
+                    good = false;
+                    break;
+                }
+                if (spins > 16) __builtin_amdgcn_s_sleep(1);
+            }
+            if (lane >= nwg || !good) g = 0ull;
+            const unsigned gh = (unsigned)(g >> 32), gl = (unsigned)g & 0xFFFFFF00u;
+            mh = wave_umax(gh);
+            ml = wave_umax(gh == mh ? gl : 0u);
+            if (touched == 0xFFFFFFFFu && seq == 0u) good = false;   // never true: keeps the touch alive
+        }
+        if (lane == 0) {
+            sh.rhi = mh;
+            sh.rlo = ml;
+            if (!good) sh.abort = 1;
+        }
+    }
+    __syncthreads();
+    hi_out = sh.rhi;
+    lo_out = sh.rlo;
+    return sh.abort == 0;
 }
 
 template <int D, int RREG, int RLDS>
@@ -103,6 +143,7 @@ select_resident(ResArgs a)
     constexpr int DW = D / 2;      // 32-bit words per key row
     constexpr int NV = DW / 4;     // 16-byte pieces per key row
     __shared__ uint4 lrows[RLDS > 0 ? RLDS * NV * 256 : 1];
+    __shared__ Shared sh;
 
     int group, member;
     if ((a.groups & 7) == 0) {
@@ -115,9 +156,10 @@ select_resident(ResArgs a)
     }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = member * 4 + (tid >> 6);
-    const int nw = a.wgpg * 4;
+    if (tid == 0) sh.abort = 0;
+    __syncthreads();
     const int rowbase = wv * (R * 64) + lane;          // this lane's r-th key is rowbase + 64 r
-    unsigned long long *gslots = a.slots + (size_t)group * 2 * kMaxWaves;
+    unsigned long long *gslots = a.slots + (size_t)group * 2 * kMaxMembers;
     const float alpha = a.alpha, oma = 1.0f - a.alpha;
     const float ninf = -__builtin_inff();
     unsigned seq = 0;
@@ -161,7 +203,7 @@ select_resident(ResArgs a)
         {
             unsigned mhi, mlo;
             const unsigned mine = wave_umax(0xFFFFFFFFu - __float_as_uint(rmin));
-            if (!exchange_max((unsigned long long)mine << 32, gslots, nw, wv, seq, lane, mhi, mlo)) goto bail;
+            if (!head_max(mine, 0u, sh, gslots, a.wgpg, member, seq, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
             rmin = __uint_as_float(0xFFFFFFFFu - mhi);
         }
 #pragma unroll
@@ -231,7 +273,7 @@ select_resident(ResArgs a)
                     }
                     unsigned mhi, mlo;
                     const unsigned mine = wave_umax(__float_as_uint(lmax));
-                    if (!exchange_max((unsigned long long)mine << 32, gslots, nw, wv, seq, lane, mhi, mlo)) goto bail;
+                    if (!head_max(mine, 0u, sh, gslots, a.wgpg, member, seq, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
                     const float dmax = __uint_as_float(mhi);
                     ainv = dmax > 0.0f ? alpha / dmax : 0.0f;
                 }
@@ -259,9 +301,8 @@ select_resident(ResArgs a)
                     const unsigned whi = wave_umax(chi);
                     const unsigned wlo = wave_umax(chi == whi ? clo : 0u);
                     unsigned mhi, mlo;
-                    if (!exchange_max(((unsigned long long)whi << 32) | wlo, gslots, nw, wv, seq, lane, mhi, mlo))
-                        goto bail;
-                    s = (int)(0xFFFFFFu - (mlo >> 8));
+                    if (!head_max(whi, wlo, sh, gslots, a.wgpg, member, seq, mhi, mlo, Kh, D, a.L - 1, true)) goto bail;
+                    s = min((int)(0xFFFFFFu - (mlo >> 8)), a.L - 1);   // in range whatever the inputs held
                     sc = __uint_as_float(mhi);
                 }
                 s = __builtin_amdgcn_readfirstlane(s);
@@ -315,7 +356,7 @@ bool pick_shape(int H, int L, int d, Shape &best)
     for (int i = 0; i < nopts; ++i) {
         const int R = opts[i][0] + opts[i][1];
         const int wgpg = (L + 256 * R - 1) / (256 * R);
-        if (wgpg * 4 > kMaxWaves) continue;
+        if (wgpg > kMaxMembers) continue;
         int groups = 512 / wgpg;
         if (groups > H) groups = H;
         if (groups >= 8) groups -= groups % 8;
@@ -347,7 +388,7 @@ size_t resident_select_workspace_bytes(int H, int L, int d)
 {
     Shape s;
     if (!pick_shape(H, L, d, s)) return 0;
-    return round_up((size_t)s.groups * 2 * kMaxWaves * sizeof(unsigned long long), 256) + 256;
+    return round_up((size_t)s.groups * 2 * kMaxMembers * sizeof(unsigned long long), 256) + 256;
 }
 
 hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
@@ -361,7 +402,7 @@ hipError_t launch_select_resident(const void *K, int H, int L, int d, const floa
     a.idx = idx;
     a.score_out = score_out;
     a.slots = reinterpret_cast<unsigned long long *>(ws);
-    const size_t nslots = (size_t)s.groups * 2 * kMaxWaves;
+    const size_t nslots = (size_t)s.groups * 2 * kMaxMembers;
     a.fail = reinterpret_cast<int *>(reinterpret_cast<char *>(ws) + round_up(nslots * sizeof(unsigned long long), 256));
     a.H = H;
     a.L = L;
