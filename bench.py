@@ -32,6 +32,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="1..5, order of the configuration list (3 = headline)")
     ap.add_argument("--heads", type=int, default=0, help="override the number of KV heads (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (written from rocprofv3 --pmc runs), if present")
     args = ap.parse_args()
@@ -114,6 +116,12 @@ def main() -> int:
         if ev:
             ev[4].record()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written by one copy kernel
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

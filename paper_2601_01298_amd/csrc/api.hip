@@ -39,7 +39,7 @@ size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, in
     switch (op) {
     case WS_OP_DENSITY:
         if (H < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
-        return ws::density_workspace_bytes(H, L);
+        return ws::density_workspace_bytes(H, L, d, dt == WS_BF16);
     case WS_OP_SELECT:
         if (H < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
         return ws::select_workspace_bytes(H, L, d, dt == WS_BF16);
@@ -58,7 +58,7 @@ ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d, co
     if (!K || !sigma_host || !rho || H < 1 || L < 1) return WS_ERR_INVALID_ARG;
     if (L >= kMaxL) return WS_ERR_UNSUPPORTED;
     if (!aligned(K, 16) || !aligned(rho, 4)) return WS_ERR_INVALID_ARG;
-    s = check_ws(workspace, workspace_bytes, ws::density_workspace_bytes(H, L));
+    s = check_ws(workspace, workspace_bytes, ws::density_workspace_bytes(H, L, d, dt == WS_BF16));
     if (s != WS_OK) return s;
     for (int h = 0; h < H; ++h) {
         const double sg = (double)sigma_host[h];

@@ -248,18 +248,225 @@ density_sweep(const typename TR::Elem *__restrict__ K, const uint4 *__restrict__
 }
 
 // ------------------------------------------------------------------------------------------
-size_t density_workspace_bytes(int H, int L)
+// Symmetric sweep (bf16 keys, heads of at least a few row blocks).
+//
+// The kernel matrix is symmetric, and its cost is the exponential, not the contraction: so every
+// unordered pair is evaluated ONCE and its value is added to the row sum of i and to the
+// column sum of j.  Keys are cut into blocks of BM rows; workgroup I evaluates block I against
+// blocks I (row sums only), I+1 .. I+nBoth (row and column sums) and, when the block count is
+// even, I + nB/2 (row sums only; its partner evaluates the transposed copy).  Every workgroup
+// does the same amount of work.  Row sums stay in registers for the whole sweep.  Column sums
+// of one visited block are reduced over the workgroup's 4 waves in LDS and written to slot
+// (J - I - 1) of a partial-sum array; a last small kernel adds row sums and slots in a fixed
+// order, so the result does not depend on scheduling.
+//
+// The 4 waves of a workgroup own different rows (RTW tiles of 32 each) and share the stream of
+// column tiles: 64 key rows per stage are copied global -> LDS with coalesced 16-byte loads,
+// double-buffered one stage ahead, and read back in MFMA operand layout (16-byte pieces,
+// XOR-swizzled by row so the 8 lanes served per LDS cycle hit 8 different bank groups).
+// ------------------------------------------------------------------------------------------
+template <int D, int RTW, bool BOTH, bool DIAG>
+__device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], const bf16x8_t (&b)[D / 16 + 1],
+                                         float (&racc)[RTW][16], float &csum, float s, int n, int hb,
+                                         int diag_rt /* row tile that meets this column tile, or -1 */)
 {
-    return round_up((size_t)H * sizeof(float), 256) + (size_t)H * density_lpad(L) * sizeof(uint4);
+    constexpr int NS = D / 16 + 1;
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt) {
+        f32x16_t acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < NS; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][kk], b[kk], acc, 0, 0, 0);
+        if (DIAG && rt == diag_rt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (8 * (r >> 2) + 4 * hb + (r & 3) == n) acc[r] = 0.0f;   // a key's distance to itself
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float w = __builtin_amdgcn_exp2f(acc[r] * s);
+            racc[rt][r] += w;
+            if (BOTH) csum += w;
+        }
+    }
 }
 
-template <class TR, int D, int RT>
-static hipError_t run(const void *K, int H, int L, const float *sigma_host, float *rho, void *ws, hipStream_t st)
+template <int D, int RTW>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const float *__restrict__ scale,
+            float *__restrict__ rowsum, float *__restrict__ colpart, int L, int Lpad, int nB, int nBoth, int head0,
+            int total)
+{
+    constexpr int NK = D / 16, NS = NK + 1;
+    constexpr int BM = 4 * RTW * 32;       // rows (and columns) per block
+    constexpr int CH = D / 8;              // 16-byte pieces per key row
+    constexpr int SC = 64;                 // key rows per LDS stage
+    constexpr int SPB = BM / SC;           // stages per block
+    constexpr int NLD = SC * CH / 256;     // 16-byte pieces each thread moves per stage
+    __shared__ uint4 sB[2][SC * CH];
+    __shared__ uint4 sE[2][SC];
+    __shared__ float cs[4][BM];
+
+    const int logical = xcd_contiguous(blockIdx.x, total);
+    const int hl = logical / nB, I = logical - hl * nB;
+    const int h = head0 + hl;
+    const uint16_t *Kh = K + (size_t)h * L * D;
+    const uint4 *exth = ext + (size_t)h * Lpad;
+    const float s = scale[h];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hb = lane >> 5;
+
+    bf16x8_t a[RTW][NS];
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt) {
+        const int row = I * BM + (wave * RTW + rt) * 32 + n;      // < Lpad
+        const uint16_t *rp = Kh + (size_t)min(row, L - 1) * D;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) a[rt][kk] = Bf16Tr::load(rp, kk, hb);
+        a[rt][NK] = Bf16Tr::ext_a(exth[row], hb, 0);
+    }
+    float racc[RTW][16];
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) racc[rt][r] = 0.0f;
+
+    const int nblk = 1 + nBoth + ((nB > 1 && (nB & 1) == 0) ? 1 : 0);
+    const int nst = nblk * SPB;
+
+    uint4 g[NLD];
+    uint4 ge = make_uint4(0, 0, 0, 0);
+    auto fetch = [&](int sidx) {       // global -> registers, coalesced
+        const int J = (I + sidx / SPB) % nB;
+        const int col0 = J * BM + (sidx % SPB) * SC;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int q = tid + 256 * i;
+            const int r = q / CH, c = q % CH;
+            g[i] = *reinterpret_cast<const uint4 *>(Kh + (size_t)min(col0 + r, L - 1) * D + c * 8);
+        }
+        if (tid < SC) ge = exth[col0 + tid];
+    };
+    auto stash = [&](int buf) {        // registers -> LDS, swizzled
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int q = tid + 256 * i;
+            const int r = q / CH, c = q % CH;
+            sB[buf][r * CH + (c ^ (r & 7))] = g[i];
+        }
+        if (tid < SC) sE[buf][tid] = ge;
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int sidx = 0; sidx < nst; ++sidx) {
+        const int buf = sidx & 1;
+        if (sidx + 1 < nst) fetch(sidx + 1);
+        const int j = sidx / SPB, sin = sidx - j * SPB;
+        const bool both = j >= 1 && j <= nBoth;
+#pragma unroll 1
+        for (int tt = 0; tt < SC / 32; ++tt) {
+            const int r = tt * 32 + n;
+            bf16x8_t b[NS];
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk)
+                b[kk] = __builtin_bit_cast(bf16x8_t, sB[buf][r * CH + ((2 * kk + hb) ^ (r & 7))]);
+            b[NK] = Bf16Tr::ext_b(sE[buf][r], hb, 0);
+            float csum = 0.0f;
+            if (j == 0) {
+                // column tile index inside the block vs this wave's row tiles
+                const int ctile = sin * (SC / 32) + tt;
+                sym_tile<D, RTW, false, true>(a, b, racc, csum, s, n, hb, ctile - wave * RTW);
+            } else if (both) {
+                sym_tile<D, RTW, true, false>(a, b, racc, csum, s, n, hb, -1);
+                csum += __shfl_xor(csum, 32);
+                if (hb == 0) cs[wave][sin * SC + r] = csum;
+            } else {
+                sym_tile<D, RTW, false, false>(a, b, racc, csum, s, n, hb, -1);
+            }
+        }
+        if (sidx + 1 < nst) stash(buf ^ 1);
+        if (both && sin == SPB - 1) {
+            __syncthreads();
+            const int J = (I + j) % nB;
+            float *dst = colpart + ((size_t)hl * nBoth + (j - 1)) * Lpad + (size_t)J * BM;
+            for (int c = tid; c < BM; c += 256) dst[c] = ((cs[0][c] + cs[1][c]) + cs[2][c]) + cs[3][c];
+        }
+        __syncthreads();
+    }
+
+    // each wave owns its rows: reduce over the 32 columns held by the lanes of a half-wave
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = racc[rt][r];
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 16);
+            if (n == 0)
+                rowsum[(size_t)hl * Lpad + I * BM + (wave * RTW + rt) * 32 + 8 * (r >> 2) + 4 * hb + (r & 3)] = v;
+        }
+}
+
+// rho = (row sum + column partial sums in slot order) / L
+__global__ void __launch_bounds__(256)
+density_finish(const float *__restrict__ rowsum, const float *__restrict__ colpart, float *__restrict__ rho, int L,
+               int Lpad, int nBoth, int head0)
+{
+    const int hl = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= L) return;
+    float t = rowsum[(size_t)hl * Lpad + i];
+    const float *cp = colpart + (size_t)hl * nBoth * Lpad + i;
+    for (int sl = 0; sl < nBoth; ++sl) t += cp[(size_t)sl * Lpad];
+    rho[(size_t)(head0 + hl) * L + i] = t / (float)L;
+}
+
+constexpr int kSymChunkHeads = 128;     // heads per symmetric launch (bounds the partial-sum workspace)
+
+static inline int sym_bm(int d) { return d == 64 ? 512 : 256; }
+static inline bool use_sym(bool bf16, int L, int d) { return bf16 && (L + sym_bm(d) - 1) / sym_bm(d) >= 4; }
+
+// ------------------------------------------------------------------------------------------
+struct DensityWs {
+    size_t scale, ext, rowsum, colpart, total;
+    int Lpad, nB, nBoth, chunk;
+};
+
+static DensityWs density_layout(int H, int L, int d, bool bf16)
+{
+    DensityWs w;
+    w.Lpad = density_lpad(L);
+    w.scale = 0;
+    w.ext = round_up((size_t)H * sizeof(float), 256);
+    w.rowsum = w.ext + (size_t)H * w.Lpad * sizeof(uint4);
+    w.total = w.rowsum;
+    w.nB = w.nBoth = w.chunk = 0;
+    w.colpart = w.rowsum;
+    if (use_sym(bf16, L, d)) {
+        w.nB = w.Lpad / sym_bm(d);
+        w.nBoth = (w.nB - 1) / 2;
+        w.chunk = H < kSymChunkHeads ? H : kSymChunkHeads;
+        w.colpart = w.rowsum + round_up((size_t)w.chunk * w.Lpad * sizeof(float), 256);
+        w.total = w.colpart + round_up((size_t)w.chunk * w.nBoth * w.Lpad * sizeof(float), 256);
+    }
+    return w;
+}
+
+size_t density_workspace_bytes(int H, int L, int d, bool bf16) { return density_layout(H, L, d, bf16).total; }
+
+template <class TR, int D>
+static void run_prep(const void *K, int H, int L, const float *sigma_host, const DensityWs &w, char *base,
+                     hipStream_t st)
 {
     typedef typename TR::Elem Elem;
-    const int Lpad = density_lpad(L);
-    float *scale = reinterpret_cast<float *>(ws);
-    uint4 *ext = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(ws) + round_up((size_t)H * sizeof(float), 256));
+    float *scale = reinterpret_cast<float *>(base + w.scale);
+    uint4 *ext = reinterpret_cast<uint4 *>(base + w.ext);
     for (int h0 = 0; h0 < H; h0 += 256) {
         const int nh = (H - h0 < 256) ? H - h0 : 256;
         ScaleChunk sc;
@@ -268,16 +475,47 @@ static hipError_t run(const void *K, int H, int L, const float *sigma_host, floa
             const double sg = (i < nh) ? (double)sigma_host[h0 + i] : 1.0;
             sc.s[i] = (float)(1.4426950408889634 / (sg * sg));
         }
-        dim3 grid((Lpad + 255) / 256, nh);
+        dim3 grid((w.Lpad + 255) / 256, nh);
         hipLaunchKernelGGL((density_prep<TR, D>), grid, dim3(256), 0, st, reinterpret_cast<const Elem *>(K), ext,
-                           scale, sc, h0, L, Lpad);
+                           scale, sc, h0, L, w.Lpad);
     }
+}
+
+template <class TR, int D, int RT>
+static hipError_t run(const void *K, int H, int L, const float *sigma_host, float *rho, void *ws, hipStream_t st)
+{
+    typedef typename TR::Elem Elem;
+    const DensityWs w = density_layout(H, L, D, sizeof(Elem) == 2);
+    char *base = reinterpret_cast<char *>(ws);
+    run_prep<TR, D>(K, H, L, sigma_host, w, base, st);
     const int BM = RT * 32;
     const int nRB = (L + BM - 1) / BM;
     const long long total = (long long)nRB * H;
     if (total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((density_sweep<TR, D, RT>), dim3((unsigned)total), dim3(256), 0, st,
-                       reinterpret_cast<const Elem *>(K), ext, scale, rho, L, Lpad, nRB, (int)total);
+                       reinterpret_cast<const Elem *>(K), reinterpret_cast<const uint4 *>(base + w.ext),
+                       reinterpret_cast<const float *>(base + w.scale), rho, L, w.Lpad, nRB, (int)total);
+    return hipGetLastError();
+}
+
+template <int D, int RTW>
+static hipError_t run_sym(const void *K, int H, int L, const float *sigma_host, float *rho, void *ws, hipStream_t st)
+{
+    const DensityWs w = density_layout(H, L, D, true);
+    char *base = reinterpret_cast<char *>(ws);
+    run_prep<Bf16Tr, D>(K, H, L, sigma_host, w, base, st);
+    float *rowsum = reinterpret_cast<float *>(base + w.rowsum);
+    float *colpart = reinterpret_cast<float *>(base + w.colpart);
+    for (int h0 = 0; h0 < H; h0 += w.chunk) {
+        const int nh = (H - h0 < w.chunk) ? H - h0 : w.chunk;
+        const int total = nh * w.nB;
+        hipLaunchKernelGGL((density_sym<D, RTW>), dim3(total), dim3(256), 0, st,
+                           reinterpret_cast<const uint16_t *>(K), reinterpret_cast<const uint4 *>(base + w.ext),
+                           reinterpret_cast<const float *>(base + w.scale), rowsum, colpart, L, w.Lpad, w.nB, w.nBoth,
+                           h0, total);
+        hipLaunchKernelGGL(density_finish, dim3((L + 255) / 256, nh), dim3(256), 0, st, rowsum, colpart, rho, L,
+                           w.Lpad, w.nBoth, h0);
+    }
     return hipGetLastError();
 }
 
@@ -285,6 +523,10 @@ hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const f
                           void *ws, hipStream_t st)
 {
     if (bf16) {
+        if (use_sym(true, L, d)) {
+            if (d == 64) return run_sym<64, 4>(K, H, L, sigma_host, rho, ws, st);
+            if (d == 128) return run_sym<128, 2>(K, H, L, sigma_host, rho, ws, st);
+        }
         if (d == 64) return run<Bf16Tr, 64, 4>(K, H, L, sigma_host, rho, ws, st);
         if (d == 128) return run<Bf16Tr, 128, 2>(K, H, L, sigma_host, rho, ws, st);
     } else {

@@ -11,9 +11,9 @@ constexpr int kWave = 64;
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
 // ---- density -------------------------------------------------------------------------
-// Keys per head are padded to a multiple of 128 in the per-key side records.
-static inline int density_lpad(int L) { return (int)round_up((size_t)L, 128); }
-size_t density_workspace_bytes(int H, int L);
+// Keys per head are padded to a multiple of 512 in the per-key side records.
+static inline int density_lpad(int L) { return (int)round_up((size_t)L, 512); }
+size_t density_workspace_bytes(int H, int L, int d, bool bf16);
 // sigma_host[h] > 0 (validated by the caller); enqueues prepass + main sweep.
 hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const float *sigma_host,
                           float *rho, void *ws, hipStream_t st);

@@ -1,0 +1,90 @@
+"""Headline workload at FULL size (24 layers x 16 KV heads -> H = 384, L = 32768, d = 64, k = 655,
+N = 100 agents, bf16), in the launch configuration bench.py times.  The oracle cannot sweep 384
+heads in a test, so: every stage is checked against the oracle on sampled heads / rows, and
+properties that hold at any size are checked on all heads."""
+import numpy as np
+import pytest
+
+from paper_2601_01298_amd import synthetic as syn
+from _util import TIE_TOL, attn_rel_err, check_indices
+
+pytestmark = pytest.mark.gpu
+
+
+def test_headline_full_size(oracle):
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2601_01298_amd import binding as ws
+    ws.lib()
+    w = syn.WORKLOADS[3]
+    sigma = np.empty(w.H, dtype=np.float32)
+
+    def fill(tensor):
+        out = np.empty((w.H, w.L, w.d), dtype=np.uint16)
+
+        def one(h):
+            x = syn.cloud(w, h, tensor)
+            if tensor == syn.TENSOR_K:
+                sigma[h] = syn.bandwidth(x)
+            out[h] = syn.bf16_bits(x)
+
+        with ThreadPoolExecutor(max_workers=16) as ex:
+            list(ex.map(one, range(w.H)))
+        return torch.from_numpy(out).view(torch.bfloat16).cuda()
+
+    K, V = fill(syn.TENSOR_K), fill(syn.TENSOR_V)
+    Qh = syn.queries(w)
+    Q = torch.from_numpy(Qh).to(torch.bfloat16).cuda()
+    print(f"inputs resident: K,V {tuple(K.shape)} bf16, Q {tuple(Q.shape)}", flush=True)
+
+    rho = ws.ws_synapse_density(K, [float(s) for s in sigma])
+    idx, score = ws.ws_synapse_select(K, rho, w.k, w.alpha, want_score=True)
+    Ks, Vs = ws.ws_synapse_gather(K, V, idx)
+    O = ws.ws_synapse_attend(Q, Ks, Vs)
+    torch.cuda.synchronize()
+    print("GPU path done", flush=True)
+
+    # ---- properties on ALL heads
+    assert float(rho.min()) >= (1.0 / w.L) * (1 - 1e-5) and float(rho.max()) <= 1.0 + 1e-5
+    assert int(idx.min()) >= 0 and int(idx.max()) < w.L
+    srt = torch.sort(idx, dim=1).values
+    assert bool((srt[:, 1:] != srt[:, :-1]).all()), "a head chose the same key twice"
+    # first pick is the lowest-density key of its head (alpha < 1): lowest index among the minima
+    first = idx[:, 0].long()
+    rmin = rho.min(dim=1).values
+    assert bool((rho.gather(1, first[:, None])[:, 0] == rmin).all())
+    assert bool((score > 0).all()) and bool((score <= 1.0 + 1e-6).all())
+    # gather is a bit copy on all heads
+    ref_Ks = torch.gather(K.view(torch.int16), 1, idx.long()[:, :, None].expand(-1, -1, w.d))
+    assert bool((ref_Ks == Ks.view(torch.int16)).all())
+    ref_Vs = torch.gather(V.view(torch.int16), 1, idx.long()[:, :, None].expand(-1, -1, w.d))
+    assert bool((ref_Vs == Vs.view(torch.int16)).all())
+    assert bool(torch.isfinite(O).all())
+
+    # ---- oracle on sampled rows: density of 16 rows in each of 8 heads
+    rng = np.random.default_rng(2026)
+    worst = 0.0
+    for h in [0, 1, 95, 191, 192, 300, 382, 383]:
+        Kh = K[h].float().cpu().numpy()
+        assert np.array_equal(Kh, syn.cloud(w, h, syn.TENSOR_K))          # same bits as the generator's
+        rows = np.concatenate([rng.integers(0, w.L, 15), idx[h, :1].cpu().numpy()]).astype(np.int32)
+        ref = oracle.density_rows(Kh, float(sigma[h]), rows)
+        worst = max(worst, float(np.abs(rho[h].cpu().numpy()[rows] / ref - 1).max()))
+    print(f"density, 8 heads x 16 rows: max rel err {worst:.2e}", flush=True)
+    assert worst <= 5e-5
+
+    # ---- oracle on sampled heads: full chain
+    for h in [0, 383, 137]:
+        Kh = K[h].float().cpu().numpy()
+        Vh = V[h].float().cpu().numpy()
+        rho_ref = oracle.density(Kh, float(sigma[h]))
+        err = float(np.abs(rho[h].cpu().numpy() / rho_ref - 1).max())
+        ref, _, gap = oracle.select(Kh, rho_ref, w.k, w.alpha)
+        forks = check_indices(oracle, Kh, rho_ref, w.k, w.alpha, idx[h].cpu().numpy(), ref)
+        ks, vs = oracle.gather(Kh, Vh, idx[h].cpu().numpy())
+        assert np.array_equal(Ks[h].float().cpu().numpy(), ks) and np.array_equal(Vs[h].float().cpu().numpy(), vs)
+        O_ref = oracle.attend(Qh[:, h:h + 1], ks[None], vs[None])
+        aerr = attn_rel_err(O[:, h:h + 1].cpu().numpy(), O_ref)
+        print(f"head {h}: density rel err {err:.2e}; oracle steps under tie tolerance {(gap < TIE_TOL).sum()}, "
+              f"forks {forks}; attention rel err {aerr:.2e}", flush=True)
+        assert err <= 5e-5 and aerr <= 2e-3
