@@ -2,7 +2,7 @@
 // context (Warp-Cortex Sec. 3.3 for the 1/sqrt(d_k) scale, Sec. 4 for the O(k) cost):
 //     O[n,q,:] = softmax_t(scale * Q[n,q,:] . Ks[h,t,:]) . Vs[h,:,:],   h = q / (Hq/Hkv).
 //
-// bf16 path: one wave owns 32 query rows of one KV head and walks the landmarks in tiles of 32.
+// bf16 path: a wave owns 32 query rows of one KV head and walks landmarks in tiles of 32.
 // Both products are computed TRANSPOSED so that a lane always owns one query:
 //     S^T = Ks_tile . Q^T     (MFMA 32x32x16: rows = landmarks, columns = queries)
 //     O^T += Vs_tile^T . P^T  (rows = head dimensions, columns = queries)
@@ -25,6 +25,8 @@ namespace ws {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
 namespace {
 
@@ -39,18 +41,47 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float f)
 // (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
 __device__ __forceinline__ int mfma_row(int r, int hb) { return 8 * (r >> 2) + 4 * hb + (r & 3); }
 
+// One workgroup = 4 waves = 2 query tiles of one KV head x 2 halves of the landmark range; the
+// workgroups of a head are placed on the same accelerator die so its K_S/V_S rows are read from HBM
+// once and from that die's L2 otherwise.  The two halves run the online softmax independently and
+// are merged through LDS at the end: that gives every SIMD the same number of equally long waves
+// (at 100 agents a head has 4 query tiles; without the split some SIMDs would carry two of them
+// and some one).  The kernel is bound by vector-ALU issue (softmax and operand shuffling), not by
+// the MFMAs or by memory, so the per-tile instruction count is what is optimised:
+//   - the score scale is folded into the exponent's FMA, the tile maximum is taken on raw scores;
+//   - the running maximum is only moved when a tile exceeds it by more than 2^8, so the
+//     accumulator is rescaled a few times per query instead of once per tile (weights stay below
+//     2^8, harmless in fp32 and in the bf16 hi+lo split);
+//   - packed conversions (v_cvt_pk_bf16_f32) and byte permutes (v_perm_b32) build the MFMA operands;
+//   - K and V operands of the next landmark tile are requested one tile ahead.
 template <int D>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
 attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, const uint16_t *__restrict__ Vs,
-            float *__restrict__ O, int N, int Hq, int Hkv, int k, float scale_log2)
+            float *__restrict__ O, int N, int Hq, int Hkv, int k, float scale_log2, int parts)
 {
     constexpr int NK = D / 16;   // k-steps of the score product
     constexpr int NP = D / 64;   // 64-wide spans of head dimensions, each an even and an odd tile
-    const int h = blockIdx.y;
+    // workgroup id -> (head, part): parts of one head sit on one die (ids are dealt to the 8 dies round-robin)
+    int h, part;
+    if ((Hkv & 7) == 0) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        h = (j / parts) * 8 + xcd;
+        part = j % parts;
+    } else {
+        h = blockIdx.x / parts;
+        part = blockIdx.x % parts;
+    }
     const int g = Hq / Hkv;
     const int M = N * g;         // query rows that read this KV head
-    const int lane = threadIdx.x, nq = lane & 31, hb = lane >> 5;
-    const int m = blockIdx.x * 32 + nq;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nq = lane & 31, hb = lane >> 5;
+    const uint16_t *Kh = Ks + (size_t)h * k * D;
+    const uint16_t *Vh = Vs + (size_t)h * k * D;
+    constexpr int NO = 2 * NP * 16;
+    __shared__ float xch[2][NO + 2][64];
+    const int wt = wave & 1, half = wave >> 1;
+    const int tile = part * 2 + wt;
+    const bool tile_live = tile * 32 < M;    // wave-uniform
+    const int m = tile * 32 + nq;
     const bool valid = m < M;
     const int mc = valid ? m : M - 1;
     const int agent = mc / g, qh = h * g + mc % g;
@@ -60,61 +91,118 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8_t *>(qrow + kk * 16 + hb * 8);
 
-    const uint16_t *Kh = Ks + (size_t)h * k * D;
-    const uint16_t *Vh = Vs + (size_t)h * k * D;
-
     f32x16_t oacc[2 * NP];
 #pragma unroll
     for (int i = 0; i < 2 * NP; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[i][r] = 0.0f;
-    float mrun = -__builtin_inff(), lrun = 0.0f;
+    float mref = -__builtin_inff();   // reference maximum (log2 units) the weights are taken against
+    float lrun = 0.0f;
 
-    for (int t0 = 0; t0 < k; t0 += 32) {
+    const int nT = (k + 31) / 32;
+    const int tA = (nT + 1) / 2;
+    const int tb = tile_live ? (half ? tA : 0) : 0;
+    const int te = tile_live ? (half ? nT : tA) : 0;
+    // Operands of the NEXT landmark tile, requested one tile ahead.  K: one 16-byte piece per k-step.
+    // V: the 32-bit word holding head dimensions (2 nq, 2 nq + 1) of 16 landmark rows; contraction slot
+    // (kk2, hb, e) <-> landmark t0 + mfma_row(8*kk2+e, hb) = t0 + 16 kk2 + 8 (e/4) + 4 hb + e%4.
+    bf16x8_t kn[NK];
+    uint32_t vn[2][NP][8];
+    auto fetch = [&](int t) {
+        const int t0 = t * 32;
+        if (t0 + 32 <= k) {      // full tile: one base address per lane, constant offsets
+            const uint16_t *krow = Kh + (size_t)(t0 + nq) * D + hb * 8;
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) kn[kk] = *reinterpret_cast<const bf16x8_t *>(krow + kk * 16);
+            const uint16_t *vbase = Vh + (size_t)(t0 + 4 * hb) * D + 2 * nq;
+#pragma unroll
+            for (int kk2 = 0; kk2 < 2; ++kk2)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int p = 0; p < NP; ++p)
+                        vn[kk2][p][e] = *reinterpret_cast<const uint32_t *>(
+                            vbase + (16 * kk2 + 8 * (e >> 2) + (e & 3)) * D + 64 * p);
+        } else {                 // ragged last tile: clamp rows into the head (their weights are zero)
+            const uint16_t *krow = Kh + (size_t)min(t0 + nq, k - 1) * D + hb * 8;
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) kn[kk] = *reinterpret_cast<const bf16x8_t *>(krow + kk * 16);
+#pragma unroll
+            for (int kk2 = 0; kk2 < 2; ++kk2)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint16_t *vrow = Vh + (size_t)min(t0 + mfma_row(8 * kk2 + e, hb), k - 1) * D + 2 * nq;
+#pragma unroll
+                    for (int p = 0; p < NP; ++p) vn[kk2][p][e] = *reinterpret_cast<const uint32_t *>(vrow + 64 * p);
+                }
+        }
+    };
+    if (tb < te) fetch(tb);
+
+    for (int t = tb; t < te; ++t) {
+        const int t0 = t * 32;
+        bf16x8_t kf[NK];
+        uint32_t vd[2][NP][8];
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) kf[kk] = kn[kk];
+#pragma unroll
+        for (int kk2 = 0; kk2 < 2; ++kk2)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vd[kk2][p][e] = vn[kk2][p][e];
+        if (t + 1 < te) fetch(t + 1);
+
         // ---- S^T tile: rows = landmarks t0..t0+31, columns = queries
-        const uint16_t *krow = Kh + (size_t)min(t0 + nq, k - 1) * D;
         f32x16_t sacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) {
-            const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(krow + kk * 16 + hb * 8);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc, 0, 0, 0);
-        }
-        // ---- online softmax, one query per lane (its other 16 landmarks sit in lane^32)
-        float x[16];
-        float tmax = -__builtin_inff();
+        for (int kk = 0; kk < NK; ++kk) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc, 0, 0, 0);
+        if (t0 + 32 > k) {       // ragged last tile: landmarks past k get zero weight
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int t = t0 + mfma_row(r, hb);
-            x[r] = (t < k) ? sacc[r] * scale_log2 : -__builtin_inff();
-            tmax = fmaxf(tmax, x[r]);
+            for (int r = 0; r < 16; ++r)
+                if (t0 + mfma_row(r, hb) >= k) sacc[r] = -__builtin_inff();
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mnew = fmaxf(mrun, tmax);
-        const float corr = __builtin_amdgcn_exp2f(mrun - mnew);
-        mrun = mnew;
+
+        // ---- online softmax, one query per lane (its other 16 landmarks sit in lane^32)
+        float tmax = sacc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[r]);
+        tmax *= scale_log2;
+        if (__any(tmax > mref + 8.0f)) {
+            // some query of this wave moved: take the exact maximum over both half-columns and rescale
+            const float tm = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float mnew = fmaxf(mref, tm);
+            const float corr = __builtin_amdgcn_exp2f(mref - mnew);     // 0 on the first tile
+            mref = mnew;
+            lrun *= corr;
+#pragma unroll
+            for (int i = 0; i < 2 * NP; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+        }
         // probabilities as bf16 hi + bf16 lo (16 significant bits): one bf16 alone would cost up to
         // 2^-9 relative error per weight, which is the whole error budget of the output
         uint32_t pkh[8], pkl[8];
         float psum = 0.0f;
+        const float nmref = -mref;
 #pragma unroll
         for (int w = 0; w < 8; ++w) {
-            const float p0 = __builtin_amdgcn_exp2f(x[2 * w] - mnew);
-            const float p1 = __builtin_amdgcn_exp2f(x[2 * w + 1] - mnew);
-            psum += p0 + p1;
-            const uint32_t h0 = __float_as_uint(p0) & 0xFFFF0000u, h1 = __float_as_uint(p1) & 0xFFFF0000u;
-            const uint32_t l0 = bf16_rne_bits(p0 - __uint_as_float(h0)), l1 = bf16_rne_bits(p1 - __uint_as_float(h1));
-            pkh[w] = (h0 >> 16) | h1;
-            pkl[w] = l0 | (l1 << 16);
+            f32x2_t pv;
+            pv[0] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w], scale_log2, nmref));
+            pv[1] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w + 1], scale_log2, nmref));
+            psum += pv[0] + pv[1];
+            const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2_t));
+            f32x2_t rest;
+            rest[0] = pv[0] - __uint_as_float(hi << 16);
+            rest[1] = pv[1] - __uint_as_float(hi & 0xFFFF0000u);
+            pkh[w] = hi;
+            pkl[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
         }
-        lrun = lrun * corr + psum;
-#pragma unroll
-        for (int i = 0; i < 2 * NP; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+        lrun += psum;
 
-        // ---- O^T += Vs^T . P^T ; contraction slot (kk2, hb, e) <-> landmark t0 + mfma_row(8*kk2+e, hb)
+        // ---- O^T += Vs^T . P^T
 #pragma unroll
         for (int kk2 = 0; kk2 < 2; ++kk2) {
             const bf16x8_t pfh = __builtin_bit_cast(
@@ -123,17 +211,12 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
                 bf16x8_t, make_uint4(pkl[4 * kk2], pkl[4 * kk2 + 1], pkl[4 * kk2 + 2], pkl[4 * kk2 + 3]));
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
-                uint32_t vd[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int t = min(t0 + mfma_row(8 * kk2 + e, hb), k - 1);
-                    vd[e] = *reinterpret_cast<const uint32_t *>(Vh + (size_t)t * D + 64 * p + 2 * nq);
-                }
                 uint32_t ev[4], od[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
-                    ev[w] = (vd[2 * w] & 0xFFFFu) | (vd[2 * w + 1] << 16);
-                    od[w] = (vd[2 * w] >> 16) | (vd[2 * w + 1] & 0xFFFF0000u);
+                    // low halves (even head dimension) and high halves (odd) of two landmark rows
+                    ev[w] = __builtin_amdgcn_perm(vd[kk2][p][2 * w + 1], vd[kk2][p][2 * w], 0x05040100u);
+                    od[w] = __builtin_amdgcn_perm(vd[kk2][p][2 * w + 1], vd[kk2][p][2 * w], 0x07060302u);
                 }
                 const bf16x8_t ve = __builtin_bit_cast(bf16x8_t, make_uint4(ev[0], ev[1], ev[2], ev[3]));
                 const bf16x8_t vo = __builtin_bit_cast(bf16x8_t, make_uint4(od[0], od[1], od[2], od[3]));
@@ -145,23 +228,42 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
         }
     }
 
-    const float l = lrun + __shfl_xor(lrun, 32);
-    if (valid) {
+    // ---- merge the two halves of the landmark range: half 1 hands its state to half 0 through LDS
+    if (half == 1) {
+        xch[wt][NO][lane] = mref;
+        xch[wt][NO + 1][lane] = lrun;
+#pragma unroll
+        for (int i = 0; i < 2 * NP; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) xch[wt][i * 16 + r][lane] = oacc[i][r];
+    }
+    __syncthreads();
+    if (half == 0 && tile_live) {
+        const float m1 = xch[wt][NO][lane], l1 = xch[wt][NO + 1][lane];
+        const float mm = fmaxf(mref, m1);                 // finite: half 0 always holds landmark 0
+        const float f0 = __builtin_amdgcn_exp2f(mref - mm), f1 = __builtin_amdgcn_exp2f(m1 - mm);
+        float l = lrun * f0 + l1 * f1;
+        l += __shfl_xor(l, 32);
         const float inv = 1.0f / l;
-        float *orow = O + ((size_t)agent * Hq + qh) * D;
+        const float g0 = f0 * inv, g1 = f1 * inv;
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
+        for (int i = 0; i < 2 * NP; ++i)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                // registers 4b..4b+3 of the even and odd tile interleave into 8 consecutive dims
-                float *dst = orow + 64 * p + 16 * b + 8 * hb;
-                const float4 lo4 = make_float4(oacc[2 * p][4 * b] * inv, oacc[2 * p + 1][4 * b] * inv,
-                                               oacc[2 * p][4 * b + 1] * inv, oacc[2 * p + 1][4 * b + 1] * inv);
-                const float4 hi4 = make_float4(oacc[2 * p][4 * b + 2] * inv, oacc[2 * p + 1][4 * b + 2] * inv,
-                                               oacc[2 * p][4 * b + 3] * inv, oacc[2 * p + 1][4 * b + 3] * inv);
-                *reinterpret_cast<float4 *>(dst) = lo4;
-                *reinterpret_cast<float4 *>(dst + 4) = hi4;
-            }
+            for (int r = 0; r < 16; ++r) oacc[i][r] = oacc[i][r] * g0 + xch[wt][i * 16 + r][lane] * g1;
+        if (valid) {
+            float *orow = O + ((size_t)agent * Hq + qh) * D;
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    // registers 4b..4b+3 of the even and odd tile interleave into 8 consecutive dims
+                    float *dst = orow + 64 * p + 16 * b + 8 * hb;
+                    *reinterpret_cast<float4 *>(dst) = make_float4(oacc[2 * p][4 * b], oacc[2 * p + 1][4 * b],
+                                                                   oacc[2 * p][4 * b + 1], oacc[2 * p + 1][4 * b + 1]);
+                    *reinterpret_cast<float4 *>(dst + 4) = make_float4(oacc[2 * p][4 * b + 2], oacc[2 * p + 1][4 * b + 2],
+                                                                       oacc[2 * p][4 * b + 3], oacc[2 * p + 1][4 * b + 3]);
+                }
+        }
     }
 }
 
@@ -233,15 +335,18 @@ hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf1
     if (bf16) {
         const int g = Hq / Hkv;
         const long long M = (long long)N * g;
-        const dim3 grid((unsigned)((M + 31) / 32), (unsigned)Hkv);
+        const long long parts = (M + 63) / 64;                 // workgroups (2 query tiles each) per head
+        const long long blocks = parts * Hkv;
+        if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)blocks);
         const float sl2 = scale * 1.4426950408889634f;
         const uint16_t *q = reinterpret_cast<const uint16_t *>(Q);
         const uint16_t *ks = reinterpret_cast<const uint16_t *>(Ks);
         const uint16_t *vs = reinterpret_cast<const uint16_t *>(Vs);
         if (d == 64)
-            hipLaunchKernelGGL(attend_bf16<64>, grid, dim3(64), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2);
+            hipLaunchKernelGGL(attend_bf16<64>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts);
         else if (d == 128)
-            hipLaunchKernelGGL(attend_bf16<128>, grid, dim3(64), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2);
+            hipLaunchKernelGGL(attend_bf16<128>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts);
         else
             return hipErrorInvalidValue;
     } else {
