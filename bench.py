@@ -170,8 +170,12 @@ def main() -> int:
         per_stage[s]["ms"] = stage_ms[s]
     dominant = max(stages, key=lambda s: stage_ms[s])
     roofline = dict(per_stage[dominant])
-    roofline["kernel"] = {"density": "density_sweep", "select": "select_stream", "gather": "gather_rows",
-                          "attend": "attend_bf16" if bf16 else "attend_f32"}[dominant]
+    kernel_of = {"density": "density_sym" if (bf16 and w.L >= 4 * (512 if w.d == 64 else 256)) else "density_sweep",
+                 "select": "select_resident" if ws.ws_synapse_select_is_resident(dt, w.H, w.L, w.d) else "select_stream",
+                 "gather": "gather_rows", "attend": "attend_bf16" if bf16 else "attend_f32"}
+    roofline["kernel"] = kernel_of[dominant]
+    for s_ in stages:
+        per_stage[s_]["kernel"] = kernel_of[s_]
 
     # ---- CPU oracle on the host's cores: one head of the same workload through all four stages
     cpu = None

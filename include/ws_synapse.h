@@ -108,6 +108,10 @@ ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dt
                             int N, int Hq, int Hkv, int k, int d, float scale, float *O,
                             void *workspace, size_t workspace_bytes, ws_stream stream);
 
+/* Which selection kernel ws_synapse_select would run for these sizes right now (the environment
+ * override included): 1 = keys resident on chip, 0 = streaming.  For reports and profiles. */
+int ws_synapse_select_is_resident(ws_dtype dt, int H, int L, int d);
+
 /* Bytes of workspace the given operation needs for these sizes (0 if none).  Arguments an
  * operation does not use are ignored.  Returns (size_t)-1 for unsupported sizes. */
 size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, int k, int N, int Hq);

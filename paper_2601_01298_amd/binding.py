@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.ws_synapse_gather.restype = ci
         L.ws_synapse_attend.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
         L.ws_synapse_attend.restype = ci
+        L.ws_synapse_select_is_resident.argtypes = [ci, ci, ci, ci]
+        L.ws_synapse_select_is_resident.restype = ci
         L.ws_status_string.argtypes = [ci]
         L.ws_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -93,6 +95,10 @@ def ws_synapse_workspace_bytes(op: int, dt: int, H: int, L: int, d: int, k: int 
     if n == ctypes.c_size_t(-1).value:
         raise WsError(WS_ERR_UNSUPPORTED, "ws_synapse_workspace_bytes")
     return int(n)
+
+
+def ws_synapse_select_is_resident(dt: int, H: int, L: int, d: int) -> bool:
+    return bool(lib().ws_synapse_select_is_resident(dt, H, L, d))
 
 
 def ws_synapse_density(K: torch.Tensor, sigma, rho: torch.Tensor | None = None, workspace=None, stream=None):

@@ -116,6 +116,12 @@ ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dt
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
 
+int ws_synapse_select_is_resident(ws_dtype dt, int H, int L, int d)
+{
+    if (check_common(dt, d) != WS_OK || H < 1 || L < 1) return 0;
+    return ws::select_uses_resident(H, L, d, dt == WS_BF16) ? 1 : 0;
+}
+
 const char *ws_status_string(ws_status s)
 {
     switch (s) {

@@ -293,7 +293,7 @@ __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], c
 }
 
 template <int D, int RTW>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((D == 64 && RTW <= 2) ? 3 : 2, (D == 64 && RTW <= 2) ? 3 : 2)))
 density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const float *__restrict__ scale,
             float *__restrict__ rowsum, float *__restrict__ colpart, int L, int Lpad, int nB, int nBoth, int head0,
             int total)
@@ -429,7 +429,8 @@ density_finish(const float *__restrict__ rowsum, const float *__restrict__ colpa
 
 constexpr int kSymChunkHeads = 128;     // heads per symmetric launch (bounds the partial-sum workspace)
 
-static inline int sym_bm(int d) { return d == 64 ? 512 : 256; }
+constexpr int kSymRtw64 = 4, kSymRtw128 = 2;   // row tiles per wave
+static inline int sym_bm(int d) { return 128 * (d == 64 ? kSymRtw64 : kSymRtw128); }
 static inline bool use_sym(bool bf16, int L, int d) { return bf16 && (L + sym_bm(d) - 1) / sym_bm(d) >= 4; }
 
 // ------------------------------------------------------------------------------------------
@@ -524,8 +525,8 @@ hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const f
 {
     if (bf16) {
         if (use_sym(true, L, d)) {
-            if (d == 64) return run_sym<64, 4>(K, H, L, sigma_host, rho, ws, st);
-            if (d == 128) return run_sym<128, 2>(K, H, L, sigma_host, rho, ws, st);
+            if (d == 64) return run_sym<64, kSymRtw64>(K, H, L, sigma_host, rho, ws, st);
+            if (d == 128) return run_sym<128, kSymRtw128>(K, H, L, sigma_host, rho, ws, st);
         }
         if (d == 64) return run<Bf16Tr, 64, 4>(K, H, L, sigma_host, rho, ws, st);
         if (d == 128) return run<Bf16Tr, 128, 2>(K, H, L, sigma_host, rho, ws, st);

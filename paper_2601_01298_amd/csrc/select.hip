@@ -337,16 +337,22 @@ static hipError_t run_select(const SelArgs &a, const SelectPlan &p, hipStream_t 
     return hipGetLastError();
 }
 
+// Keys that fit on chip are selected by the resident kernel; the environment variable
+// WS_SYNAPSE_SELECT=stream|resident overrides the choice (testing, profiling).
+bool select_uses_resident(int H, int L, int d, bool bf16)
+{
+    const char *force = getenv("WS_SYNAPSE_SELECT");
+    if (force && force[0] == 's') return false;
+    return resident_select_supported(H, L, d, bf16);
+}
+
 hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k, float alpha,
                          int32_t *idx, float *score_out, void *ws, hipStream_t st)
 {
-    // Keys that fit on chip are selected by the resident kernel; the environment variable
-    // WS_SYNAPSE_SELECT=stream|resident overrides the choice (testing, profiling).
-    const char *force = getenv("WS_SYNAPSE_SELECT");
     const bool can_res = resident_select_supported(H, L, d, bf16);
-    bool use_res = can_res;
-    if (force && force[0] == 's') use_res = false;
+    const char *force = getenv("WS_SYNAPSE_SELECT");
     if (force && force[0] == 'r' && !can_res) return hipErrorInvalidValue;
+    const bool use_res = select_uses_resident(H, L, d, bf16);
     if (use_res) return launch_select_resident(K, H, L, d, rho, k, alpha, idx, score_out, ws, st);
 
     const SelectPlan p = select_plan(H, L, d, bf16);

@@ -26,6 +26,8 @@ struct SelectPlan {
 };
 SelectPlan select_plan(int H, int L, int d, bool bf16);
 size_t select_workspace_bytes(int H, int L, int d, bool bf16);
+// the choice launch_select makes (environment override WS_SYNAPSE_SELECT included)
+bool select_uses_resident(int H, int L, int d, bool bf16);
 hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
                          float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st);
 
