@@ -110,12 +110,20 @@ density_prep(const typename TR::Elem *__restrict__ K, uint4 *__restrict__ ext, f
     if (j >= Lpad) return;
     uint4 rec;
     if (j < L) {
-        const typename TR::Elem *row = K + ((size_t)h * L + j) * D;
+        // whole row through 16-byte loads (a thread owns a row: 8 or more loads hit the same lines)
+        const uint4 *row = reinterpret_cast<const uint4 *>(K + ((size_t)h * L + j) * D);
+        constexpr int PER = 16 / sizeof(typename TR::Elem);
         double n = 0.0;
-#pragma unroll 8
-        for (int c = 0; c < D; ++c) {
-            const double x = TR::widen(row[c]);
-            n += x * x;
+#pragma unroll 4
+        for (int c = 0; c < D / PER; ++c) {
+            const uint4 q = row[c];
+            typename TR::Elem e[PER];
+            __builtin_memcpy(e, &q, 16);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const double x = TR::widen(e[i]);
+                n += x * x;
+            }
         }
         double x = -0.5 * n;
         if constexpr (sizeof(typename TR::Elem) == 2) {
