@@ -193,25 +193,34 @@ select_stream(SelArgs a)
                     float lm[PER];
                     Row<T>::unpack(*reinterpret_cast<const uint4 *>(Kh + (size_t)prev * D + sub * PER), lm);
                     float lmax = 0.0f;
-                    for (int r0 = lo; r0 < hi; r0 += RPI) {
-                        const int i = r0 + rsub;
-                        const int ic = min(i, hi - 1);
-                        float f[PER];
-                        Row<T>::unpack(*reinterpret_cast<const uint4 *>(Kh + (size_t)ic * D + sub * PER), f);
-                        float acc = 0.0f;
+                    constexpr int UN = 4;      // key rows in flight per lane: the sweep is latency-bound otherwise
+                    for (int r0 = lo; r0 < hi; r0 += UN * RPI) {
+                        uint4 q[UN];
+                        float dold[UN];
 #pragma unroll
-                        for (int c = 0; c < PER; ++c) {
-                            const float df = f[c] - lm[c];
-                            acc = fmaf(df, df, acc);
+                        for (int u = 0; u < UN; ++u) {
+                            const int i = r0 + u * RPI + rsub;
+                            const int ic = min(i, hi - 1);
+                            q[u] = *reinterpret_cast<const uint4 *>(Kh + (size_t)ic * D + sub * PER);
+                            dold[u] = (sub == 0) ? Dg[ic] : 0.0f;
                         }
 #pragma unroll
-                        for (int o = 1; o < LPR; o <<= 1) acc += __shfl_xor(acc, o);
-                        if (sub == 0 && i < hi) {
-                            const float dold = Dg[i];
-                            if (dold >= 0.0f) {
+                        for (int u = 0; u < UN; ++u) {
+                            const int i = r0 + u * RPI + rsub;
+                            float f[PER];
+                            Row<T>::unpack(q[u], f);
+                            float acc = 0.0f;
+#pragma unroll
+                            for (int c = 0; c < PER; ++c) {
+                                const float df = f[c] - lm[c];
+                                acc = fmaf(df, df, acc);
+                            }
+#pragma unroll
+                            for (int o = 1; o < LPR; o <<= 1) acc += __shfl_xor(acc, o);
+                            if (sub == 0 && i < hi && dold[u] >= 0.0f) {
                                 const float dist = __fsqrt_rn(acc);
-                                float dn = dold;
-                                if (dist < dold) {
+                                float dn = dold[u];
+                                if (dist < dn) {
                                     dn = dist;
                                     Dg[i] = dist;
                                 }

@@ -133,6 +133,56 @@ def test_select_with_near_tie_forks(ws, oracle, cfg, H, L, k, select_kernel):
         print(f"cfg{cfg} head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
 
 
+def test_select_streaming_at_long_context_size(ws, oracle, monkeypatch):
+    """Head size of the long-context configuration (L = 131072, d = 128: too large to sit on chip, so
+    the streaming kernel with 64 workgroups per head runs).  A full oracle density at this size takes
+    minutes, so the density handed to both sides is synthetic (any positive array is a valid input of
+    the selection); the chain is shortened to k = 200."""
+    import torch
+    monkeypatch.delenv("WS_SYNAPSE_SELECT", raising=False)
+    w = variant(5, H=2, L=131072, k=200)
+    rng = np.random.default_rng(77)
+    K = np.stack([syn.cloud(w, h, syn.TENSOR_K) for h in range(w.H)])
+    rho = rng.uniform(0.05, 1.0, size=(w.H, w.L)).astype(np.float32)
+    Kd = to_device(K, w.dtype)
+    assert not ws.ws_synapse_select_is_resident(ws.WS_BF16, w.H, w.L, w.d)
+    idx = ws.ws_synapse_select(Kd, torch.from_numpy(rho).cuda(), w.k, w.alpha).cpu().numpy()
+    for h in range(w.H):
+        ref, _, gap = oracle.select(K[h], rho[h], w.k, w.alpha)
+        forks = check_indices(oracle, K[h], rho[h], w.k, w.alpha, idx[h], ref)
+        print(f"L=131072 head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
+
+
+def test_chain_scale_out_config_heads(ws, oracle, select_kernel):
+    """Agent scale-out configuration at its full head size (L = 8192, d = 128, k = 164, N = 1000),
+    8 of its 32 heads: density, selection (near-tie protocol: its outliers tie by construction),
+    gather, and 1000-agent attention."""
+    w = variant(4, H=8, Hq=8)
+    K = np.stack([syn.cloud(w, h, syn.TENSOR_K) for h in range(w.H)])
+    V = np.stack([syn.cloud(w, h, syn.TENSOR_V) for h in range(w.H)])
+    Qh = syn.queries(w)
+    sigma = [syn.bandwidth(K[h]) for h in range(w.H)]
+    Kd, Vd = to_device(K, w.dtype), to_device(V, w.dtype)
+    rho = ws.ws_synapse_density(Kd, sigma)
+    idx = ws.ws_synapse_select(Kd, rho, w.k, w.alpha)
+    Ks, Vs = ws.ws_synapse_gather(Kd, Vd, idx)
+    O = ws.ws_synapse_attend(to_device(Qh, w.dtype), Ks, Vs).cpu().numpy()
+    idx = idx.cpu().numpy()
+    Ks_ref = np.empty((w.H, w.k, w.d), dtype=np.float32)
+    Vs_ref = np.empty_like(Ks_ref)
+    for h in range(w.H):
+        rho_ref = oracle.density(K[h], float(sigma[h]))
+        assert np.abs(rho[h].cpu().numpy() / rho_ref - 1).max() <= RHO_TOL[w.dtype]
+        ref, _, gap = oracle.select(K[h], rho_ref, w.k, w.alpha)
+        forks = check_indices(oracle, K[h], rho_ref, w.k, w.alpha, idx[h], ref)
+        print(f"scale-out head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
+        Ks_ref[h], Vs_ref[h] = oracle.gather(K[h], V[h], idx[h])
+    assert np.array_equal(Ks.float().cpu().numpy(), Ks_ref) and np.array_equal(Vs.float().cpu().numpy(), Vs_ref)
+    err = attn_rel_err(O, oracle.attend(Qh, Ks_ref, Vs_ref))
+    print(f"scale-out: attention rel err {err:.2e} (N={w.N})")
+    assert err <= ATT_TOL[w.dtype]
+
+
 def test_select_edge_cases(ws, oracle, select_kernel):
     import torch
     # k = L on a small cloud: a permutation, and the zero-radius tail of duplicates
