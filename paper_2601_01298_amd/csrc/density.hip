@@ -279,23 +279,41 @@ __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], c
                                          int diag_rt /* row tile that meets this column tile, or -1 */)
 {
     constexpr int NS = D / 16 + 1;
+    // The contraction of row tile rt+1 is issued before the exponentials of row tile rt, one MFMA per
+    // slice of the vector work, so the matrix core runs under the vector pipe inside one wave.
+    f32x16_t acc[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][r] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < NS; ++kk) acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][kk], b[kk], acc[0], 0, 0, 0);
 #pragma unroll
     for (int rt = 0; rt < RTW; ++rt) {
-        f32x16_t acc;
+        f32x16_t &cur = acc[rt & 1], &nxt = acc[(rt + 1) & 1];
+        if (rt + 1 < RTW) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            for (int r = 0; r < 16; ++r) nxt[r] = 0.0f;
 #pragma unroll
-        for (int kk = 0; kk < NS; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][kk], b[kk], acc, 0, 0, 0);
+            for (int kk = 0; kk < NS; ++kk)
+                nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt + 1][kk], b[kk], nxt, 0, 0, 0);
+        }
         if (DIAG && rt == diag_rt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + 4 * hb + (r & 3) == n) acc[r] = 0.0f;   // a key's distance to itself
+                if (8 * (r >> 2) + 4 * hb + (r & 3) == n) cur[r] = 0.0f;   // a key's distance to itself
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float w = __builtin_amdgcn_exp2f(acc[r] * s);
+            const float w = __builtin_amdgcn_exp2f(cur[r] * s);
             racc[rt][r] += w;
             if (BOTH) csum += w;
+        }
+        if (!DIAG && rt + 1 < RTW) {
+            constexpr int VPER = (BOTH ? 64 : 48) / NS;      // vector instructions between two MFMAs
+#pragma unroll
+            for (int kk = 0; kk < NS; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);
+            }
         }
     }
 }
@@ -437,7 +455,7 @@ density_finish(const float *__restrict__ rowsum, const float *__restrict__ colpa
 
 constexpr int kSymChunkHeads = 128;     // heads per symmetric launch (bounds the partial-sum workspace)
 
-constexpr int kSymRtw64 = 4, kSymRtw128 = 2;   // row tiles per wave
+constexpr int kSymRtw64 = 2, kSymRtw128 = 2;   // row tiles per wave
 static inline int sym_bm(int d) { return 128 * (d == 64 ? kSymRtw64 : kSymRtw128); }
 static inline bool use_sym(bool bf16, int L, int d) { return bf16 && (L + sym_bm(d) - 1) / sym_bm(d) >= 4; }
 
