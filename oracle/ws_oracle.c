@@ -42,6 +42,28 @@
  *   R8  attention: z_t = (q . K_S[t]) * scale, softmax over the k landmarks,
  *       no mask, O = sum_t p_t V_S[t]; query head q reads KV head q / (Hq/Hkv).
  *
+ * Steps next to the hot path (built after it), each with its own reading:
+ *
+ *   R9  attention mass (Sec. 3.3, "Attention Score Summation"): the printed
+ *       formula sums a softmax over the heads of one layer but names no token
+ *       axis.  Reading: per query head q of the layer, softmax over the L cached
+ *       tokens of z_{q,i} = scale * (Q_q . K_{kv(q),i}), kv(q) = q / (Hq/Hkv);
+ *       A_i = sum over the layer's query heads of that softmax.  sum_i A_i = Hq.
+ *   R10 the same passage calls A the INVERSE density estimator: the array handed
+ *       to the selection in place of rho is 1 / max(A_i, 1e-30), so that
+ *       u_i = A_i / A_max.
+ *   R11 validation gate (Sec. 3.5 and its equation): cosine similarity of each
+ *       side thought's hidden state with the main agent's; a thought passes when
+ *       score >= theta (the text rejects score < theta); a zero vector scores 0.
+ *   R12 referential injection (Sec. 3.6): the appended key rows are rotated by
+ *       RoPE at a caller-given virtual position p before they join the cache,
+ *       values join unchanged.  Convention (the paper's model family): pairs
+ *       (c, c + d/2), angle p * base^(-2c/d), c < d/2:
+ *         y_c = x_c cos - x_{c+d/2} sin,   y_{c+d/2} = x_{c+d/2} cos + x_c sin.
+ *   R13 refresh while the main agent decodes (Sec. 4, the listing's main-stream
+ *       loop): the density of the grown context is R1 on the grown cloud; an
+ *       incremental update must reproduce it, so its oracle is wso_density.
+ *
  * Pins (see tests/test_oracle_pins.py): two-point and three-point closed forms
  * of the density, scipy logsumexp/cdist, per-step exhaustive re-evaluation of
  * the score from its definition on tiny clouds, Gonzalez farthest-point
@@ -273,6 +295,70 @@ int wso_attend(const double *Q, const double *Ks, const double *Vs,
         free(z);
     }
     return fail ? -1 : 0;
+}
+
+/* R9.  K [Hkv,L,d], Q [Hq,d] of ONE layer -> A [L].  Serial over heads so the sum order is fixed. */
+int wso_attention_mass(const double *K, const double *Q, int Hkv, int Hq, int L, int d, double scale, double *A)
+{
+    if (Hkv < 1 || Hq < 1 || L < 1 || d < 1 || Hq % Hkv != 0) return -1;
+    const int g = Hq / Hkv;
+    double *z = (double *)malloc(sizeof(double) * (size_t)L);
+    if (!z) return -1;
+    for (int i = 0; i < L; ++i) A[i] = 0.0;
+    for (int q = 0; q < Hq; ++q) {
+        const double *Kh = K + (size_t)(q / g) * L * d;
+        const double *qv = Q + (size_t)q * d;
+        double zmax = -WSO_INF;
+        for (int i = 0; i < L; ++i) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c) s += qv[c] * Kh[(size_t)i * d + c];
+            z[i] = s * scale;
+            if (z[i] > zmax) zmax = z[i];
+        }
+        double den = 0.0;
+        for (int i = 0; i < L; ++i) { z[i] = exp(z[i] - zmax); den += z[i]; }
+        for (int i = 0; i < L; ++i) A[i] += z[i] / den;
+    }
+    free(z);
+    return 0;
+}
+
+/* R10.  The array that replaces rho in the selection. */
+void wso_mass_to_density(const double *A, int L, double *rho)
+{
+    for (int i = 0; i < L; ++i) rho[i] = 1.0 / (A[i] > 1e-30 ? A[i] : 1e-30);
+}
+
+/* R11.  hmain [dm], T [N,dm] -> score [N], accept [N] (1 = passes). */
+void wso_gate(const double *hmain, const double *T, int N, int dm, double theta, double *score, int32_t *accept)
+{
+    double nh = 0.0;
+    for (int c = 0; c < dm; ++c) nh += hmain[c] * hmain[c];
+    nh = sqrt(nh);
+    for (int n = 0; n < N; ++n) {
+        const double *t = T + (size_t)n * dm;
+        double dot = 0.0, nt = 0.0;
+        for (int c = 0; c < dm; ++c) { dot += hmain[c] * t[c]; nt += t[c] * t[c]; }
+        nt = sqrt(nt);
+        score[n] = (nh > 0.0 && nt > 0.0) ? dot / (nh * nt) : 0.0;
+        accept[n] = score[n] >= theta ? 1 : 0;
+    }
+}
+
+/* R12.  X [m,d] rows, pos [m] virtual positions -> Y [m,d] rotated rows. */
+int wso_rope(const double *X, const int32_t *pos, int m, int d, double base, double *Y)
+{
+    if (m < 0 || d < 2 || (d & 1) || !(base > 0.0)) return -1;
+    const int half = d / 2;
+    for (int r = 0; r < m; ++r)
+        for (int c = 0; c < half; ++c) {
+            const double ang = (double)pos[r] * pow(base, -2.0 * (double)c / (double)d);
+            const double cs = cos(ang), sn = sin(ang);
+            const double x0 = X[(size_t)r * d + c], x1 = X[(size_t)r * d + c + half];
+            Y[(size_t)r * d + c] = x0 * cs - x1 * sn;
+            Y[(size_t)r * d + c + half] = x1 * cs + x0 * sn;
+        }
+    return 0;
 }
 
 int wso_num_threads(void)

@@ -52,6 +52,14 @@ def _load():
         L.wso_gather.restype = None
         L.wso_attend.argtypes = [dp, dp, dp] + [ctypes.c_int] * 5 + [ctypes.c_double, dp]
         L.wso_attend.restype = ctypes.c_int
+        L.wso_attention_mass.argtypes = [dp, dp] + [ctypes.c_int] * 4 + [ctypes.c_double, dp]
+        L.wso_attention_mass.restype = ctypes.c_int
+        L.wso_mass_to_density.argtypes = [dp, ctypes.c_int, dp]
+        L.wso_mass_to_density.restype = None
+        L.wso_gate.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp, ip]
+        L.wso_gate.restype = None
+        L.wso_rope.argtypes = [dp, ip, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp]
+        L.wso_rope.restype = ctypes.c_int
         L.wso_num_threads.argtypes = []
         L.wso_num_threads.restype = ctypes.c_int
         _lib = L
@@ -157,6 +165,51 @@ def attend(Q, Ks, Vs, scale: float | None = None) -> np.ndarray:
     if rc != 0:
         raise ValueError("wso_attend rejected its arguments")
     return O
+
+
+def attention_mass(K, Q, scale: float | None = None) -> np.ndarray:
+    """One layer: K [Hkv,L,d], Q [Hq,d] -> A [L] (sum over query heads of the softmax over tokens)."""
+    K = _f64(K)
+    Q = _f64(Q)
+    Hkv, L, d = K.shape
+    Hq = Q.shape[0]
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    A = np.empty(L, dtype=np.float64)
+    rc = _load().wso_attention_mass(_dp(K), _dp(Q), Hkv, Hq, L, d, float(scale), _dp(A))
+    if rc != 0:
+        raise ValueError("wso_attention_mass rejected its arguments")
+    return A
+
+
+def mass_to_density(A) -> np.ndarray:
+    A = _f64(A)
+    rho = np.empty_like(A)
+    _load().wso_mass_to_density(_dp(A), A.shape[0], _dp(rho))
+    return rho
+
+
+def gate(hmain, T, theta: float):
+    """hmain [dm], T [N,dm] -> (score [N] float64, accept [N] int32)."""
+    hmain = _f64(hmain)
+    T = _f64(T)
+    N, dm = T.shape
+    score = np.empty(N, dtype=np.float64)
+    accept = np.empty(N, dtype=np.int32)
+    _load().wso_gate(_dp(hmain), _dp(T), N, dm, float(theta), _dp(score), _ip(accept))
+    return score, accept
+
+
+def rope(X, pos, base: float = 10000.0) -> np.ndarray:
+    """X [m,d], pos [m] -> rows rotated at their virtual positions, float64."""
+    X = _f64(X)
+    m, d = X.shape
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    Y = np.empty_like(X)
+    rc = _load().wso_rope(_dp(X), _ip(pos), m, d, float(base), _dp(Y))
+    if rc != 0:
+        raise ValueError("wso_rope rejected its arguments")
+    return Y
 
 
 if __name__ == "__main__":
