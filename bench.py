@@ -32,6 +32,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="1..5, order of the configuration list (3 = headline)")
     ap.add_argument("--heads", type=int, default=0, help="override the number of KV heads (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--no-next", action="store_true", help="skip timing the steps next to the hot path")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
@@ -177,6 +178,71 @@ def main() -> int:
     for s_ in stages:
         per_stage[s_]["kernel"] = kernel_of[s_]
 
+    # ---- the steps next to the hot path, at this workload's shapes (outside the timed region above)
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]))
+
+    next_steps = {}
+    if not args.no_next:
+        G = w.layers
+        Qm = torch.from_numpy(syn.main_query(w))
+        Qm = (Qm.to(torch.bfloat16) if bf16 else Qm).cuda()
+        ws_mass = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_ATTENTION_MASS, dt, w.H, w.L, w.d, Hq=w.Hq),
+                              dtype=torch.uint8, device=dev)
+        rho_m = torch.empty_like(rho)
+        ms = timed(lambda: ws.ws_synapse_attention_mass(K, Qm, G, out=rho_m, workspace=ws_mass))
+        nbytes = float(w.H) * w.L * w.d * esize + 4.0 * w.H * w.L
+        next_steps["attention_mass"] = {"ms": ms, "bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9,
+                                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "kernel": "mass_logits",
+                                        "shape": f"G={G} Hkv={w.H // G} Hq={w.Hq // G} L={w.L} d={w.d}"}
+        del ws_mass, rho_m
+        ws_app = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_DENSITY_APPEND, dt, w.H, w.L, w.d),
+                             dtype=torch.uint8, device=dev)
+        rho_old = rho[:, :w.L - 1].contiguous()
+        rho_n = torch.empty_like(rho)
+        ms = timed(lambda: ws.ws_synapse_density_append(K, 1, sig_list, rho_old, rho_new=rho_n, workspace=ws_app))
+        nbytes = float(w.H) * w.L * w.d * esize + 8.0 * w.H * w.L
+        next_steps["density_append"] = {"ms": ms, "bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9,
+                                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "kernel": "append_sweep",
+                                        "shape": f"H={w.H} L={w.L} d={w.d} m=1"}
+        del ws_app, rho_old, rho_n
+        dm = 896
+        hm, Ts = syn.hidden_states(w.N, dm, w.dtype)
+        hm, Ts = torch.from_numpy(hm), torch.from_numpy(Ts)
+        hm, Ts = ((hm.to(torch.bfloat16), Ts.to(torch.bfloat16)) if bf16 else (hm, Ts))
+        hm, Ts = hm.cuda(), Ts.cuda()
+        sc_g = torch.empty(w.N, dtype=torch.float32, device=dev)
+        ac_g = torch.empty(w.N, dtype=torch.int32, device=dev)
+        ms = timed(lambda: ws.ws_synapse_gate(hm, Ts, 0.5, score=sc_g, accept=ac_g), reps=20)
+        nbytes = float(w.N + 1) * dm * esize + 8.0 * w.N
+        next_steps["gate"] = {"ms": ms, "bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "kernel": "gate_rows", "shape": f"N={w.N} dm={dm}",
+                              "note": "a few hundred KB: launch-latency sized"}
+        m_inj, cap = 16, 64
+        Kn, Vn, pos = syn.thought_rows(w, m_inj)
+        Kn, Vn = torch.from_numpy(Kn), torch.from_numpy(Vn)
+        Kn, Vn = ((Kn.to(torch.bfloat16), Vn.to(torch.bfloat16)) if bf16 else (Kn, Vn))
+        Kn, Vn, pos = Kn.cuda(), Vn.cuda(), torch.from_numpy(pos).cuda()
+        Kcache = torch.zeros((w.H, cap, w.d), dtype=K.dtype, device=dev)
+        Vcache = torch.zeros_like(Kcache)
+        ws_inj = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_INJECT, dt, w.H, cap, w.d, k=m_inj),
+                             dtype=torch.uint8, device=dev)
+        ms = timed(lambda: ws.ws_synapse_inject(Kcache, Vcache, 8, Kn, Vn, pos, 1.0e6, workspace=ws_inj), reps=20)
+        nbytes = 4.0 * w.H * m_inj * w.d * esize
+        next_steps["inject"] = {"ms": ms, "bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "kernel": "inject_rows", "shape": f"H={w.H} m={m_inj} d={w.d}",
+                                "note": "two small launches: launch-latency sized"}
+        for v in next_steps.values():
+            v["frac"] = v["achieved"] / v["peak"]
+
     # ---- CPU oracle on the host's cores: one head of the same workload through all four stages
     cpu = None
     if not args.no_cpu_baseline:
@@ -218,6 +284,7 @@ def main() -> int:
         "stage_ms": stage_ms,
         "roofline": roofline,
         "stages": per_stage,
+        "next_steps": next_steps,
         "cpu_baseline": cpu,
         "input_generation_s": gen_s,
         "context": "paper reports memory only: 100 agents in 2.2 GB total VRAM on an RTX 4090 (abstract, Table 2)",

@@ -46,7 +46,12 @@ typedef enum {
 
 typedef enum { WS_F32 = 0, WS_BF16 = 1 } ws_dtype;
 
-typedef enum { WS_OP_DENSITY = 0, WS_OP_SELECT = 1, WS_OP_GATHER = 2, WS_OP_ATTEND = 3 } ws_op;
+typedef enum {
+    WS_OP_DENSITY = 0, WS_OP_SELECT = 1, WS_OP_GATHER = 2, WS_OP_ATTEND = 3,
+    WS_OP_ATTENTION_MASS = 4,  /* H = G*Hkv heads, Hq = query heads per group times G */
+    WS_OP_DENSITY_APPEND = 5,  /* k = m appended rows */
+    WS_OP_INJECT = 6           /* k = m injected rows */
+} ws_op;
 
 typedef void *ws_stream; /* hipStream_t */
 
@@ -106,6 +111,70 @@ ws_status ws_synapse_gather(const void *K, const void *V, ws_dtype dt, int H, in
  */
 ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dtype dt,
                             int N, int Hq, int Hkv, int k, int d, float scale, float *O,
+                            void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Steps next to the hot path.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Attention-mass density proxy (Sec. 3.3, "Attention Score Summation"): the density ingredient
+ * taken from the main agent's current query instead of a kernel density over the keys, at
+ * O(L d) per head instead of O(L^2 d).  Heads come in G groups (layers) of Hkv KV heads and Hq
+ * query heads, Hq % Hkv == 0, query head q of a group reading KV head q / (Hq/Hkv).  Per group,
+ *     A_i = sum_{q < Hq} softmax_i( scale * Q[q,:] . K[kv(q), i, :] ),   softmax over the L tokens,
+ * so sum_i A_i = Hq.  The passage uses A as the INVERSE density: with as_density != 0 the value
+ * written is 1 / max(A_i, 1e-30), which ws_synapse_select takes in place of rho (u_i = A_i/A_max);
+ * with as_density == 0 it is A_i itself.
+ *   K   dev [G*Hkv, L, d];  Q dev [G*Hq, d] (one query token per head), both dtype `dt`
+ *   out dev [G*Hkv, L] fp32: every KV head of a group receives the group's values
+ *   Hq <= 128 per group, Hq/Hkv <= 8;  scale <= 0 means 1/sqrt(d)
+ */
+ws_status ws_synapse_attention_mass(const void *K, const void *Q, ws_dtype dt, int G, int Hkv, int Hq,
+                                    int L, int d, float scale, int as_density, float *out,
+                                    void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/*
+ * Density refresh after the context has grown by m rows (Sec. 4: the main stream re-extracts
+ * landmarks inside its decode loop).  K holds the L rows AFTER the append, the new ones last;
+ * rho_old is the density of the first L-m rows (from ws_synapse_density or an earlier refresh,
+ * same sigma).  L*rho is a plain sum of kernel values, so
+ *     rho_new[j] = ((L-m) * rho_old[j] + sum_{r<m} w(j, L-m+r)) / L            j < L-m
+ *     rho_new[L-m+r] = (sum_{j<L} w(j, L-m+r)) / L                             r < m
+ * with w(i,j) = exp(-||K_i-K_j||^2 / (2 sigma^2)); distances by direct differences in fp32.
+ * Cost O(L m d) per head.  Each refresh adds fp32 rounding to the old entries; a full
+ * ws_synapse_density at every re-selection sheds it.
+ *   K dev [H,L,d];  1 <= m <= 32, m < L;  sigma_host host [H];  rho_old dev [H,L-m];  rho_new dev [H,L]
+ */
+ws_status ws_synapse_density_append(const void *K, ws_dtype dt, int H, int L, int d, int m,
+                                    const float *sigma_host, const float *rho_old, float *rho_new,
+                                    void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/*
+ * Validation gate (Sec. 3.5 and its equation): cosine similarity between the main agent's hidden
+ * state and each side agent's thought vector; a thought passes when the score reaches theta.
+ *     score[n] = (h . T[n]) / (||h|| ||T[n]||)   (0 when either norm is 0),  accept[n] = score[n] >= theta
+ *   h_main dev [dm];  T dev [N,dm], dtype `dt`, 4-byte aligned rows at least (16-byte aligned rows
+ *   are read with wide loads);  score dev [N] fp32;  accept dev [N] int32 (1 = passes)
+ * The decision is taken on the fp32 score that is written.
+ */
+ws_status ws_synapse_gate(const void *h_main, const void *T, ws_dtype dt, int N, int dm, float theta,
+                          float *score, int32_t *accept, ws_stream stream);
+
+/*
+ * Referential injection, cache side (Sec. 3.6): m key/value rows computed elsewhere for a side
+ * agent's thought join the main agent's cache in place.  The keys are rotated by RoPE at
+ * caller-given virtual positions, the values are copied; rows 0..L-1 are not touched.
+ *     pairs (c, c+d/2), angle a = pos[r] * base^(-2c/d):
+ *     Kc[h,L+r,c] = x_c cos a - x_{c+d/2} sin a,   Kc[h,L+r,c+d/2] = x_{c+d/2} cos a + x_c sin a
+ * Angles are formed in float64 and reduced before the fp32 sine/cosine, so positions up to 2^31
+ * keep full accuracy.
+ *   Kc, Vc dev [H,Lcap,d] caches with L rows in use, L + m <= Lcap
+ *   Knew, Vnew dev [H,m,d] un-rotated rows;  pos dev [m] int32;  base > 0 (e.g. 1e6)
+ *   workspace: cos/sin table of the m positions
+ */
+ws_status ws_synapse_inject(void *Kc, void *Vc, ws_dtype dt, int H, int Lcap, int d, int L,
+                            const void *Knew, const void *Vnew, int m, const int32_t *pos, float base,
                             void *workspace, size_t workspace_bytes, ws_stream stream);
 
 /* Which selection kernel ws_synapse_select would run for these sizes right now (the environment

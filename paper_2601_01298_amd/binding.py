@@ -15,6 +15,7 @@ import torch
 WS_OK, WS_ERR_INVALID_ARG, WS_ERR_UNSUPPORTED, WS_ERR_WORKSPACE, WS_ERR_HIP = range(5)
 WS_F32, WS_BF16 = 0, 1
 WS_OP_DENSITY, WS_OP_SELECT, WS_OP_GATHER, WS_OP_ATTEND = range(4)
+WS_OP_ATTENTION_MASS, WS_OP_DENSITY_APPEND, WS_OP_INJECT = 4, 5, 6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libws_synapse.so")
@@ -47,6 +48,14 @@ def lib() -> ctypes.CDLL:
         L.ws_synapse_gather.restype = ci
         L.ws_synapse_attend.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
         L.ws_synapse_attend.restype = ci
+        L.ws_synapse_attention_mass.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, vp, sz, vp]
+        L.ws_synapse_attention_mass.restype = ci
+        L.ws_synapse_density_append.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.POINTER(cf), vp, vp, vp, sz, vp]
+        L.ws_synapse_density_append.restype = ci
+        L.ws_synapse_gate.argtypes = [vp, vp, ci, ci, ci, cf, vp, vp, vp]
+        L.ws_synapse_gate.restype = ci
+        L.ws_synapse_inject.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp, vp, ci, vp, cf, vp, sz, vp]
+        L.ws_synapse_inject.restype = ci
         L.ws_synapse_select_is_resident.argtypes = [ci, ci, ci, ci]
         L.ws_synapse_select_is_resident.restype = ci
         L.ws_status_string.argtypes = [ci]
@@ -170,3 +179,79 @@ def ws_synapse_attend(Q: torch.Tensor, Ks: torch.Tensor, Vs: torch.Tensor, scale
     _check(lib().ws_synapse_attend(Q.data_ptr(), Ks.data_ptr(), Vs.data_ptr(), dt, N, Hq, Hkv, k, d, float(scale),
                                    _dev(O, "O").data_ptr(), wptr, wlen, _stream(stream)), "ws_synapse_attend")
     return O
+
+
+def ws_synapse_attention_mass(K: torch.Tensor, Q: torch.Tensor, G: int, scale: float = 0.0, as_density: bool = True,
+                              out: torch.Tensor | None = None, workspace=None, stream=None):
+    """K [G*Hkv,L,d], Q [G*Hq,d] -> out [G*Hkv,L] fp32 (1/A when as_density, else A)."""
+    _dev(K, "K")
+    _dev(Q, "Q")
+    GHkv, L, d = K.shape
+    GHq = Q.shape[0]
+    if GHkv % G or GHq % G:
+        raise ValueError("head counts must be multiples of the number of groups")
+    dt = _dtype_code(K)
+    if out is None:
+        out = torch.empty((GHkv, L), dtype=torch.float32, device=K.device)
+    need = ws_synapse_workspace_bytes(WS_OP_ATTENTION_MASS, dt, GHkv, L, d, Hq=GHq)
+    workspace = _workspace(need, K.device, workspace)
+    _check(lib().ws_synapse_attention_mass(K.data_ptr(), Q.data_ptr(), dt, G, GHkv // G, GHq // G, L, d, float(scale),
+                                           int(bool(as_density)), _dev(out, "out").data_ptr(), workspace.data_ptr(),
+                                           workspace.numel(), _stream(stream)), "ws_synapse_attention_mass")
+    return out
+
+
+def ws_synapse_density_append(K: torch.Tensor, m: int, sigma, rho_old: torch.Tensor, rho_new: torch.Tensor | None = None,
+                              workspace=None, stream=None):
+    """K [H,L,d] with the m new rows last, rho_old [H,L-m] -> rho_new [H,L]."""
+    _dev(K, "K")
+    _dev(rho_old, "rho_old")
+    H, L, d = K.shape
+    dt = _dtype_code(K)
+    if tuple(rho_old.shape) != (H, L - m) or rho_old.dtype != torch.float32:
+        raise ValueError("rho_old must be fp32 [H, L-m]")
+    sig = (ctypes.c_float * H)(*[float(s) for s in sigma])
+    if rho_new is None:
+        rho_new = torch.empty((H, L), dtype=torch.float32, device=K.device)
+    need = ws_synapse_workspace_bytes(WS_OP_DENSITY_APPEND, dt, H, L, d)
+    workspace = _workspace(need, K.device, workspace)
+    _check(lib().ws_synapse_density_append(K.data_ptr(), dt, H, L, d, int(m), sig, rho_old.data_ptr(),
+                                           _dev(rho_new, "rho_new").data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                           _stream(stream)), "ws_synapse_density_append")
+    return rho_new
+
+
+def ws_synapse_gate(h_main: torch.Tensor, T: torch.Tensor, theta: float, score: torch.Tensor | None = None,
+                    accept: torch.Tensor | None = None, stream=None):
+    """h_main [dm], T [N,dm] -> (score [N] fp32, accept [N] int32)."""
+    _dev(h_main, "h_main")
+    _dev(T, "T")
+    N, dm = T.shape
+    dt = _dtype_code(T)
+    if h_main.dtype != T.dtype or h_main.numel() != dm:
+        raise ValueError("h_main must have T's element type and dm elements")
+    if score is None:
+        score = torch.empty(N, dtype=torch.float32, device=T.device)
+    if accept is None:
+        accept = torch.empty(N, dtype=torch.int32, device=T.device)
+    _check(lib().ws_synapse_gate(h_main.data_ptr(), T.data_ptr(), dt, N, dm, float(theta), _dev(score, "score").data_ptr(),
+                                 _dev(accept, "accept").data_ptr(), _stream(stream)), "ws_synapse_gate")
+    return score, accept
+
+
+def ws_synapse_inject(Kc: torch.Tensor, Vc: torch.Tensor, L: int, Knew: torch.Tensor, Vnew: torch.Tensor,
+                      pos: torch.Tensor, base: float, workspace=None, stream=None):
+    """Kc,Vc [H,Lcap,d] caches with L rows in use; Knew,Vnew [H,m,d]; pos [m] int32.  Writes rows L..L+m-1."""
+    for t, name in ((Kc, "Kc"), (Vc, "Vc"), (Knew, "Knew"), (Vnew, "Vnew"), (pos, "pos")):
+        _dev(t, name)
+    H, Lcap, d = Kc.shape
+    m = Knew.shape[1]
+    dt = _dtype_code(Kc)
+    if pos.dtype != torch.int32 or pos.numel() != m or tuple(Knew.shape) != (H, m, d) or Knew.dtype != Kc.dtype:
+        raise ValueError("shape or type mismatch")
+    need = ws_synapse_workspace_bytes(WS_OP_INJECT, dt, H, Lcap, d, k=m)
+    workspace = _workspace(need, Kc.device, workspace)
+    _check(lib().ws_synapse_inject(Kc.data_ptr(), Vc.data_ptr(), dt, H, Lcap, d, int(L), Knew.data_ptr(), Vnew.data_ptr(),
+                                   m, pos.data_ptr(), float(base), workspace.data_ptr(), workspace.numel(),
+                                   _stream(stream)), "ws_synapse_inject")
+    return L + m

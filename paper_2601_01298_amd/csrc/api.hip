@@ -32,9 +32,7 @@ extern "C" {
 
 size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, int k, int N, int Hq)
 {
-    (void)k;
     (void)N;
-    (void)Hq;
     if (check_common(dt, d) != WS_OK) return (size_t)-1;
     switch (op) {
     case WS_OP_DENSITY:
@@ -46,6 +44,16 @@ size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, in
     case WS_OP_GATHER:
     case WS_OP_ATTEND:
         return 0;
+    case WS_OP_ATTENTION_MASS:
+        // H = KV heads in all groups, Hq = query heads in all groups: per-head logits and tile partials
+        if (H < 1 || Hq < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
+        return ws::mass_workspace_bytes(1, Hq, L);
+    case WS_OP_DENSITY_APPEND:
+        if (H < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
+        return ws::append_workspace_bytes(H, L);
+    case WS_OP_INJECT:
+        if (k < 1) return (size_t)-1;
+        return ws::inject_workspace_bytes(d, k);
     }
     return (size_t)-1;
 }
@@ -113,6 +121,76 @@ ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dt
     if (!std::isfinite(scale)) return WS_ERR_INVALID_ARG;
     if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)d);
     const hipError_t e = ws::launch_attend(Q, Ks, Vs, dt == WS_BF16, N, Hq, Hkv, k, d, scale, O, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_attention_mass(const void *K, const void *Q, ws_dtype dt, int G, int Hkv, int Hq, int L, int d,
+                                    float scale, int as_density, float *out, void *workspace, size_t workspace_bytes,
+                                    ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!K || !Q || !out || G < 1 || Hkv < 1 || Hq < 1 || L < 1 || Hq % Hkv != 0) return WS_ERR_INVALID_ARG;
+    if (!std::isfinite(scale) || !aligned(K, 16) || !aligned(Q, 16) || !aligned(out, 4)) return WS_ERR_INVALID_ARG;
+    if (L >= kMaxL || !ws::mass_supported(Hkv, Hq) || (long long)G * Hkv > 65535 || (long long)G * Hq > (1 << 20))
+        return WS_ERR_UNSUPPORTED;
+    if (G > 65535) return WS_ERR_UNSUPPORTED;
+    s = check_ws(workspace, workspace_bytes, ws::mass_workspace_bytes(G, Hq, L));
+    if (s != WS_OK) return s;
+    if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)d);
+    const hipError_t e = ws::launch_attention_mass(K, Q, dt == WS_BF16, G, Hkv, Hq, L, d, scale, as_density, out,
+                                                   workspace, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_density_append(const void *K, ws_dtype dt, int H, int L, int d, int m, const float *sigma_host,
+                                    const float *rho_old, float *rho_new, void *workspace, size_t workspace_bytes,
+                                    ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!K || !sigma_host || !rho_old || !rho_new || H < 1 || L < 2 || m < 1 || m >= L) return WS_ERR_INVALID_ARG;
+    if (L >= kMaxL || m > ws::append_max_rows()) return WS_ERR_UNSUPPORTED;
+    if (!aligned(K, 16) || !aligned(rho_old, 4) || !aligned(rho_new, 4)) return WS_ERR_INVALID_ARG;
+    s = check_ws(workspace, workspace_bytes, ws::append_workspace_bytes(H, L));
+    if (s != WS_OK) return s;
+    for (int h = 0; h < H; ++h) {
+        const double sg = (double)sigma_host[h];
+        const float sc = (float)(0.5 * 1.4426950408889634 / (sg * sg));
+        if (!(sg > 0.0) || !std::isfinite(sg) || !std::isfinite(sc) || sc <= 0.0f) return WS_ERR_INVALID_ARG;
+    }
+    const hipError_t e = ws::launch_density_append(K, dt == WS_BF16, H, L, d, m, sigma_host, rho_old, rho_new,
+                                                   workspace, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_gate(const void *h_main, const void *T, ws_dtype dt, int N, int dm, float theta, float *score,
+                          int32_t *accept, ws_stream stream)
+{
+    if (dt != WS_F32 && dt != WS_BF16) return WS_ERR_UNSUPPORTED;
+    if (!h_main || !T || !score || !accept || N < 1 || dm < 1 || std::isnan(theta)) return WS_ERR_INVALID_ARG;
+    const size_t es = dt == WS_BF16 ? 2 : 4;
+    if (!aligned(h_main, es) || !aligned(T, es) || !aligned(score, 4) || !aligned(accept, 4)) return WS_ERR_INVALID_ARG;
+    if ((long long)(N + 3) / 4 > 0x7FFFFFFFLL) return WS_ERR_UNSUPPORTED;
+    const hipError_t e = ws::launch_gate(h_main, T, dt == WS_BF16, N, dm, theta, score, accept, (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_inject(void *Kc, void *Vc, ws_dtype dt, int H, int Lcap, int d, int L, const void *Knew,
+                            const void *Vnew, int m, const int32_t *pos, float base, void *workspace,
+                            size_t workspace_bytes, ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!Kc || !Vc || !Knew || !Vnew || !pos || H < 1 || Lcap < 1 || L < 0 || m < 1) return WS_ERR_INVALID_ARG;
+    if ((long long)L + m > Lcap || !(base > 0.0f) || !std::isfinite(base)) return WS_ERR_INVALID_ARG;
+    if (!aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(Knew, 16) || !aligned(Vnew, 16) || !aligned(pos, 4))
+        return WS_ERR_INVALID_ARG;
+    if ((long long)m * (d / 2) > (1 << 28)) return WS_ERR_UNSUPPORTED;
+    s = check_ws(workspace, workspace_bytes, ws::inject_workspace_bytes(d, m));
+    if (s != WS_OK) return s;
+    const hipError_t e = ws::launch_inject(Kc, Vc, dt == WS_BF16, H, Lcap, d, L, Knew, Vnew, m, pos, base, workspace,
+                                           (hipStream_t)stream);
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
 

@@ -45,6 +45,24 @@ hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int
 hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq,
                          int Hkv, int k, int d, float scale, float *O, hipStream_t st);
 
+// ---- steps next to the hot path -------------------------------------------------------
+bool mass_supported(int Hkv, int Hq);
+size_t mass_workspace_bytes(int G, int Hq, int L);
+hipError_t launch_attention_mass(const void *K, const void *Q, bool bf16, int G, int Hkv, int Hq, int L, int d,
+                                 float scale, int as_density, float *out, void *ws, hipStream_t st);
+
+int append_max_rows();
+size_t append_workspace_bytes(int H, int L);
+hipError_t launch_density_append(const void *K, bool bf16, int H, int L, int d, int m, const float *sigma_host,
+                                 const float *rho_old, float *rho_new, void *ws, hipStream_t st);
+
+hipError_t launch_gate(const void *hmain, const void *T, bool bf16, int N, int dm, float theta, float *score,
+                       int32_t *accept, hipStream_t st);
+
+size_t inject_workspace_bytes(int d, int m);
+hipError_t launch_inject(void *Kc, void *Vc, bool bf16, int H, int Lcap, int d, int L, const void *Knew,
+                         const void *Vnew, int m, const int32_t *pos, float base, void *ws, hipStream_t st);
+
 // Workgroup ids are handed to the 8 accelerator dies (XCDs) round-robin, and each die has
 // its own L2.  This maps a hardware workgroup id to a logical id so that each die works on
 // one contiguous range of logical ids (neighbouring tiles of the same head share an L2).

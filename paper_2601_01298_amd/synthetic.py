@@ -149,3 +149,35 @@ def clouds(w: Workload, tensor: int, heads=None, seeds=None, threads: int = 8, o
     with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
         list(ex.map(one, enumerate(heads)))
     return out
+
+
+# ---- inputs of the steps next to the hot path (attention mass, gate, injection) ---------------
+def main_query(w: Workload, seed: int = BASE_SEED) -> np.ndarray:
+    """[Hq,d] float32: the main agent's current query token, one row per query head ~ N(0, I)."""
+    rng = _rng(seed, w.cfg, 1, TENSOR_Q)
+    return _store(rng.standard_normal((w.Hq, w.d), dtype=np.float32), w.dtype)
+
+
+def hidden_states(N: int, dm: int, dtype: str, seed: int = BASE_SEED):
+    """(h_main [dm], T [N,dm]) float32: final-layer hidden states of the main agent and of N side
+    thoughts.  Thought n is a mix a_n * h + noise with a_n spread over [-0.5, 3], so the cosine
+    scores cover both sides of any threshold; thought 0 is all zeros (a degenerate case)."""
+    rng = _rng(seed, 0, 2, TENSOR_AUX)
+    h = rng.standard_normal(dm)
+    a = rng.uniform(-0.5, 3.0, size=(N, 1))
+    T = a * h + rng.standard_normal((N, dm))
+    T[0] = 0.0
+    return _store(h, dtype), _store(T, dtype)
+
+
+def thought_rows(w: Workload, m: int, seed: int = BASE_SEED):
+    """(Knew, Vnew [H,m,d], pos [m] int32): un-rotated key/value rows of an injected thought and
+    the virtual positions given to them (spread from small indices to far beyond the context)."""
+    rng = _rng(seed, w.cfg, 3, TENSOR_AUX)
+    Kn = _store(2.0 * rng.standard_normal((w.H, m, w.d), dtype=np.float32), w.dtype)
+    Vn = _store(2.0 * rng.standard_normal((w.H, m, w.d), dtype=np.float32), w.dtype)
+    pos = np.sort(rng.integers(0, 4 * max(w.L, 1024), size=m)).astype(np.int32)
+    pos[0] = 0
+    if m > 1:
+        pos[-1] = 2_000_000_000
+    return Kn, Vn, pos

@@ -92,3 +92,41 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert A(fake, fake, fake, b.WS_BF16, 0, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
     assert A(fake, fake, fake, b.WS_BF16, 4, 4, 4, 10, 64, float("inf"), fake, None, 0, None) == b.WS_ERR_INVALID_ARG
     assert A(fake, fake, None, b.WS_BF16, 4, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
+
+
+def test_bad_arguments_of_the_next_steps_are_rejected_on_the_host(lib):
+    from paper_2601_01298_amd import binding as b
+    vp = ctypes.c_void_p
+    fake, odd = vp(0x1000), vp(0x1004)
+    big = 1 << 40
+    sig = (ctypes.c_float * 2)(1.0, 1.0)
+    bad_sig = (ctypes.c_float * 2)(1.0, -1.0)
+    M = lib.ws_synapse_attention_mass
+    assert M(fake, fake, b.WS_BF16, 2, 4, 6, 100, 64, 0.0, 1, fake, fake, big, None) == b.WS_ERR_INVALID_ARG     # 6 % 4
+    assert M(fake, None, b.WS_BF16, 2, 4, 4, 100, 64, 0.0, 1, fake, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert M(fake, odd, b.WS_BF16, 2, 4, 4, 100, 64, 0.0, 1, fake, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert M(fake, fake, b.WS_BF16, 2, 4, 64, 100, 64, 0.0, 1, fake, fake, big, None) == b.WS_ERR_UNSUPPORTED    # 16 per KV head
+    assert M(fake, fake, b.WS_BF16, 2, 4, 4, 100, 80, 0.0, 1, fake, fake, big, None) == b.WS_ERR_UNSUPPORTED
+    assert M(fake, fake, b.WS_BF16, 2, 4, 4, 100, 64, 0.0, 1, fake, fake, 64, None) == b.WS_ERR_WORKSPACE
+    A = lib.ws_synapse_density_append
+    assert A(fake, b.WS_BF16, 2, 100, 64, 0, sig, fake, fake, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert A(fake, b.WS_BF16, 2, 100, 64, 100, sig, fake, fake, fake, big, None) == b.WS_ERR_INVALID_ARG          # no old rows
+    assert A(fake, b.WS_BF16, 2, 100, 64, 33, sig, fake, fake, fake, big, None) == b.WS_ERR_UNSUPPORTED
+    assert A(fake, b.WS_BF16, 2, 100, 64, 4, bad_sig, fake, fake, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert A(fake, b.WS_BF16, 2, 100, 64, 4, sig, None, fake, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert A(fake, b.WS_BF16, 2, 100, 64, 4, sig, fake, fake, None, 0, None) == b.WS_ERR_WORKSPACE
+    G = lib.ws_synapse_gate
+    assert G(fake, fake, b.WS_BF16, 0, 896, 0.5, fake, fake, None) == b.WS_ERR_INVALID_ARG
+    assert G(fake, None, b.WS_BF16, 4, 896, 0.5, fake, fake, None) == b.WS_ERR_INVALID_ARG
+    assert G(fake, fake, b.WS_BF16, 4, 896, float("nan"), fake, fake, None) == b.WS_ERR_INVALID_ARG
+    assert G(fake, fake, 5, 4, 896, 0.5, fake, fake, None) == b.WS_ERR_UNSUPPORTED
+    I = lib.ws_synapse_inject
+    assert I(fake, fake, b.WS_BF16, 2, 100, 64, 98, fake, fake, 3, fake, 1e4, fake, big, None) == b.WS_ERR_INVALID_ARG   # no room
+    assert I(fake, fake, b.WS_BF16, 2, 100, 64, 10, fake, fake, 3, fake, 0.0, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert I(fake, fake, b.WS_BF16, 2, 100, 64, 10, fake, fake, 3, None, 1e4, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert I(fake, odd, b.WS_BF16, 2, 100, 64, 10, fake, fake, 3, fake, 1e4, fake, big, None) == b.WS_ERR_INVALID_ARG
+    assert I(fake, fake, b.WS_BF16, 2, 100, 96, 10, fake, fake, 3, fake, 1e4, fake, big, None) == b.WS_ERR_UNSUPPORTED
+    assert I(fake, fake, b.WS_BF16, 2, 100, 64, 10, fake, fake, 3, fake, 1e4, None, 0, None) == b.WS_ERR_WORKSPACE
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_INJECT, b.WS_BF16, 2, 100, 64, k=3) >= 3 * 32 * 8
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTENTION_MASS, b.WS_BF16, 8, 4096, 64, Hq=8) >= 8 * 4096 * 4
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY_APPEND, b.WS_BF16, 8, 4096, 64) > 0
