@@ -88,3 +88,38 @@ def test_headline_full_size(oracle):
         print(f"head {h}: density rel err {err:.2e}; oracle steps under tie tolerance {(gap < TIE_TOL).sum()}, "
               f"forks {forks}; attention rel err {aerr:.2e}", flush=True)
         assert err <= 5e-5 and aerr <= 2e-3
+
+    # ---- the steps next to the hot path at the same full size
+    # attention mass: all 24 layers in one call; oracle on 3 whole layers, sum rule on all
+    G, Hl = w.layers, w.H // w.layers
+    Qm_h = syn.main_query(w)
+    Qm = torch.from_numpy(Qm_h).to(torch.bfloat16).cuda()
+    A = ws.ws_synapse_attention_mass(K, Qm, G, as_density=False)
+    tot = A.view(G, Hl, w.L)[:, 0].double().sum(dim=1).cpu().numpy()
+    assert np.abs(tot - Hl).max() < 1e-3 * Hl, "attention mass of a layer must sum to its number of query heads"
+    worst = 0.0
+    for grp in [0, 11, 23]:
+        Kg = K[grp * Hl:(grp + 1) * Hl].float().cpu().numpy()
+        ref = oracle.attention_mass(Kg, Qm_h[grp * Hl:(grp + 1) * Hl])
+        got = A[grp * Hl].double().cpu().numpy()
+        big = ref > 1e-12 * ref.max()
+        worst = max(worst, float(np.abs(got[big] / ref[big] - 1).max()))
+    print(f"attention mass, 3 of {G} layers: max rel err {worst:.2e}", flush=True)
+    assert worst <= 1e-4
+
+    # density refresh: the last 3 rows of every head treated as just appended; oracle on sampled rows
+    m = 3
+    sig = [float(s) for s in sigma]
+    rho_old = ws.ws_synapse_density(K[:, :w.L - m].contiguous(), sig)
+    rho_new = ws.ws_synapse_density_append(K, m, sig, rho_old)
+    diff = float((rho_new / rho - 1).abs().max())
+    print(f"density refresh (m={m}) vs full density on all {w.H} heads: max rel diff {diff:.2e}", flush=True)
+    assert diff <= 1e-4                                   # two GPU paths, each within 5e-5 of the oracle
+    worst = 0.0
+    for h in [0, 200, 383]:
+        Kh = K[h].float().cpu().numpy()
+        rows = np.concatenate([rng.integers(0, w.L - m, 13), np.arange(w.L - m, w.L)]).astype(np.int32)
+        ref = oracle.density_rows(Kh, sig[h], rows)
+        worst = max(worst, float(np.abs(rho_new[h].cpu().numpy()[rows] / ref - 1).max()))
+    print(f"density refresh, 3 heads x 16 rows (new rows included): max rel err {worst:.2e}", flush=True)
+    assert worst <= 5e-5
