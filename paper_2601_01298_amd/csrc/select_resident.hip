@@ -9,14 +9,19 @@
 // touches HBM again until the next head.  The landmark row is fetched once per step through
 // the scalar cache into SGPRs and used as a broadcast operand.
 //
-// A head is shared by up to 32 workgroups of 4 waves, placed on one accelerator die.  Twice per
-// step the head needs a maximum over all its keys (D_max, then the best candidate).  Each is
-// reduced in three levels: lanes of a wave with DPP row operations, the waves of a workgroup
-// through LDS, and the workgroups of the head through one tagged 64-bit slot each in global
-// memory, posted and polled by a single wave per workgroup (keeping the number of requests that
-// hit the slots' L2 channel small matters more than saving a barrier).  Waits are bounded; a
-// workgroup whose wait expires raises the failure flag, and (if it is the head's writer) writes -1
-// into the index entries still owed, then leaves.
+// A head is shared by up to 32 workgroups of 4 waves, placed on one accelerator die.  A step needs
+// two maxima over all keys of the head, the second depending on the first: D_max, then the best
+// score alpha*D/D_max + (1-alpha)*u.  D_max rarely changes from one step to the next (the far
+// point that sets it stays uncovered for long stretches), so every workgroup scores its keys with
+// the PREVIOUS step's D_max and sends its local D maximum and its candidate in ONE exchange; only
+// when the new D_max differs from the guess are the candidates recomputed and exchanged again
+// (same arithmetic either way, so the picks do not depend on the guess).  An exchange reduces in
+// three levels: lanes of a wave with DPP row operations, the waves of a workgroup through LDS, and
+// the workgroups of the head through two tagged 64-bit slots each in global memory, posted and
+// polled by a single wave per workgroup (keeping the number of requests that hit the slots' L2
+// channel small matters more than saving a barrier).  Waits are bounded; a workgroup whose wait
+// expires raises the failure flag, and (if it is the head's writer) writes -1 into the index entries
+// still owed, then leaves.
 #include "ws_internal.h"
 
 namespace ws {
@@ -31,7 +36,7 @@ struct ResArgs {
     const float *rho;
     int32_t *idx;
     float *score_out;
-    unsigned long long *slots;   // [groups][2][kMaxMembers]
+    unsigned long long *slots;   // [groups][2 phases][2 kinds][kMaxMembers]
     int *fail;
     int H, L, k;
     int groups, wgpg;            // heads in flight, workgroups per head
@@ -61,53 +66,66 @@ __device__ __forceinline__ unsigned wave_umax(unsigned v)
 }
 
 struct Shared {
-    unsigned hi[4], lo[4];     // one (hi, lo) pair per wave of the workgroup
-    unsigned rhi, rlo;         // result of the exchange
+    unsigned dm[4], hi[4], lo[4];   // one entry per wave of the workgroup
+    unsigned rdm, rhi, rlo;         // result of the exchange
     int abort;
 };
 
-// Maximum of a (hi, lo) pair -- compared as one 64-bit number, lo has its low 8 bits clear --
-// over every wave of the head.  Three levels: lanes of a wave (done by the caller, `hi`/`lo` are
-// wave-uniform), the 4 waves of a workgroup through LDS, the workgroups of the head through one
-// tagged 64-bit slot each in global memory.  Only wave 0 of a workgroup touches the slots, and
-// only with `nwg` lanes, so a poll round of a whole head costs nwg*nwg small requests at the L2
-// instead of (4 nwg)^2 * 16.  `pf`, if not null, is the key row of this workgroup's candidate:
-// wave 0 touches it after posting, so that it is in this die's L2 when the winner is fetched.
+// One exchange over every wave of the head, carrying two independent maxima:
+//   dm        a 32-bit value (D_max as float bits, or any other unsigned quantity);
+//   (hi, lo)  a candidate compared as one 64-bit number, lo with its low 8 bits clear
+//             (score bits, then the complemented index so that the lowest index wins ties).
+// Three levels: lanes of a wave (done by the caller, the inputs are wave-uniform), the 4 waves of a
+// workgroup through LDS, the workgroups of the head through two tagged 64-bit slots each in global
+// memory.  Only wave 0 of a workgroup touches the slots: lanes 0 and 1 post, lane j polls slot A of
+// member j and lane 32+j slot B, so a poll round of a whole head costs 2*nwg*nwg small requests at
+// the L2 instead of (4 nwg)^2 * 16.  With `prefetch`, wave 0 touches the key row of this workgroup's
+// candidate after posting, so that it is in this die's L2 when the winner is fetched.
 // Returns false (for every thread of the workgroup) if the bounded wait expired.
-__device__ __forceinline__ bool head_max(unsigned hi, unsigned lo, Shared &sh, unsigned long long *gslots, int nwg,
-                                         int member, unsigned &seq, unsigned &hi_out, unsigned &lo_out,
-                                         const uint16_t *pf_base, int D, int last_row, bool prefetch)
+__device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, Shared &sh, unsigned long long *gslots,
+                                         int nwg, int member, unsigned &seq, unsigned &dm_out, unsigned &hi_out,
+                                         unsigned &lo_out, const uint16_t *pf_base, int D, int last_row, bool prefetch)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (lane == 0) {
+        sh.dm[wave] = dm;
         sh.hi[wave] = hi;
         sh.lo[wave] = lo;
     }
     __syncthreads();
     if (wave == 0) {
+        const unsigned d4 = lane < 4 ? sh.dm[lane] : 0u;
         const unsigned h4 = lane < 4 ? sh.hi[lane] : 0u, l4 = lane < 4 ? sh.lo[lane] : 0u;
+        unsigned md = wave_umax(d4);
         unsigned mh = wave_umax(h4);
         unsigned ml = wave_umax(h4 == mh ? l4 : 0u);
         bool good = true;
         if (nwg > 1) {
             ++seq;
             const unsigned tag = seq % 255u + 1u;
-            unsigned long long *slot = gslots + (seq & 1u) * kMaxMembers;
-            if (lane == 0)
-                __hip_atomic_store(slot + member, ((unsigned long long)mh << 32) | ml | tag, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            unsigned long long *slot = gslots + (seq & 1u) * 2 * kMaxMembers;   // [kind][member]
+            // Per-lane addresses are rebuilt from the lane id on every call: kept live across the
+            // whole step loop they would be spilled and reloaded on this, the latency-critical path.
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            if (ln < 2) {
+                const unsigned long long word =
+                    ln == 0 ? (((unsigned long long)md << 32) | tag) : (((unsigned long long)mh << 32) | ml | tag);
+                __hip_atomic_store(slot + ln * kMaxMembers + member, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             unsigned touched = 0u;
-            if (prefetch && lane < D / 8) {
+            if (prefetch && ln < D / 8) {
                 // candidate index travels in bits 8..31 of lo, complemented
                 const int cand = min((int)(0xFFFFFFu - (ml >> 8)), last_row);
-                touched = *reinterpret_cast<const volatile unsigned *>(pf_base + (size_t)cand * D + lane * 8);
+                touched = *reinterpret_cast<const volatile unsigned *>(pf_base + (size_t)cand * D + ln * 8);
             }
-            bool ok = lane >= nwg;
+            const int who = ln & 31, kind = ln >> 5;
+            bool ok = who >= nwg;
             unsigned long long g = 0ull;
             unsigned spins = 0;
             while (true) {
                 if (!ok) {
-                    g = __hip_atomic_load(slot + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    g = __hip_atomic_load(slot + kind * kMaxMembers + who, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     ok = (unsigned)(g & 0xFFull) == tag;
                 }
                 if (__all(ok)) break;
@@ -117,19 +135,22 @@ __device__ __forceinline__ bool head_max(unsigned hi, unsigned lo, Shared &sh, u
                 }
                 if (spins > 16) __builtin_amdgcn_s_sleep(1);
             }
-            if (lane >= nwg || !good) g = 0ull;
+            if (who >= nwg || !good) g = 0ull;
             const unsigned gh = (unsigned)(g >> 32), gl = (unsigned)g & 0xFFFFFF00u;
-            mh = wave_umax(gh);
-            ml = wave_umax(gh == mh ? gl : 0u);
+            md = wave_umax(kind == 0 ? gh : 0u);
+            mh = wave_umax(kind == 1 ? gh : 0u);
+            ml = wave_umax((kind == 1 && gh == mh) ? gl : 0u);
             if (touched == 0xFFFFFFFFu && seq == 0u) good = false;   // never true: keeps the touch alive
         }
         if (lane == 0) {
+            sh.rdm = md;
             sh.rhi = mh;
             sh.rlo = ml;
             if (!good) sh.abort = 1;
         }
     }
     __syncthreads();
+    dm_out = sh.rdm;
     hi_out = sh.rhi;
     lo_out = sh.rlo;
     return sh.abort == 0;
@@ -159,7 +180,7 @@ select_resident(ResArgs a)
     if (tid == 0) sh.abort = 0;
     __syncthreads();
     const int rowbase = wv * (R * 64) + lane;          // this lane's r-th key is rowbase + 64 r
-    unsigned long long *gslots = a.slots + (size_t)group * 2 * kMaxMembers;
+    unsigned long long *gslots = a.slots + (size_t)group * 4 * kMaxMembers;
     const float alpha = a.alpha, oma = 1.0f - a.alpha;
     const float ninf = -__builtin_inff();
     unsigned seq = 0;
@@ -201,10 +222,10 @@ select_resident(ResArgs a)
             if (row < a.L) rmin = fminf(rmin, rh[r]);
         }
         {
-            unsigned mhi, mlo;
+            unsigned mdm, mhi, mlo;
             const unsigned mine = wave_umax(0xFFFFFFFFu - __float_as_uint(rmin));
-            if (!head_max(mine, 0u, sh, gslots, a.wgpg, member, seq, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
-            rmin = __uint_as_float(0xFFFFFFFFu - mhi);
+            if (!head_max(mine, 0u, 0u, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
+            rmin = __uint_as_float(0xFFFFFFFFu - mdm);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -215,8 +236,9 @@ select_resident(ResArgs a)
 
         {
             int prev = 0;
+            unsigned dprev = 0xFFFFFFFFu;    // bits of the D_max the last step ended with (none yet)
             for (t = 0; t < a.k; ++t) {
-                float ainv = alpha;          // step 0: coverage term is 1 for every key
+                unsigned lbits = 0u;
                 if (t > 0) {
                     // ---- distance of every resident key to landmark `prev`
                     float acc[R];
@@ -271,11 +293,7 @@ select_resident(ResArgs a)
                         Dv[r] = fminf(Dv[r], __fsqrt_rn(acc[r]));    // chosen keys stay at -1
                         lmax = fmaxf(lmax, Dv[r]);
                     }
-                    unsigned mhi, mlo;
-                    const unsigned mine = wave_umax(__float_as_uint(lmax));
-                    if (!head_max(mine, 0u, sh, gslots, a.wgpg, member, seq, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
-                    const float dmax = __uint_as_float(mhi);
-                    ainv = dmax > 0.0f ? alpha / dmax : 0.0f;
+                    lbits = wave_umax(__float_as_uint(lmax));
                 }
 
                 int s;
@@ -284,24 +302,33 @@ select_resident(ResArgs a)
                     s = 0;
                     sc = alpha;
                 } else {
-                    // ---- score = alpha * D/D_max + (1-alpha) * u ; keys in ascending order per lane
-                    float best = -1.0f;
-                    int bi = 0;
+                    // ---- score = alpha * D/D_max + (1-alpha) * u ; keys in ascending order per lane.
+                    // First with the D_max of the previous step (step 0: coverage term 1 for every key),
+                    // sent together with this step's local D maximum; again only if D_max moved.
+                    unsigned mdm = 0u, mhi = 0u, mlo = 0u;
+                    for (int pass = 0; pass < 2; ++pass) {
+                        const float dmax = __uint_as_float(dprev);
+                        const float ainv = (t == 0) ? alpha : (dmax > 0.0f ? alpha / dmax : 0.0f);
+                        float best = -1.0f;
+                        int bi = 0;
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const float dd = (t == 0) ? 1.0f : Dv[r];
-                        const float v = fmaf(ainv, dd, ou[r]);
-                        if (v > best) {
-                            best = v;
-                            bi = rowbase + 64 * r;
+                        for (int r = 0; r < R; ++r) {
+                            const float dd = (t == 0) ? 1.0f : Dv[r];
+                            const float v = fmaf(ainv, dd, ou[r]);
+                            if (v > best) {
+                                best = v;
+                                bi = rowbase + 64 * r;
+                            }
                         }
+                        const unsigned chi = best >= 0.0f ? __float_as_uint(best) : 0u;
+                        const unsigned clo = best >= 0.0f ? (0xFFFFFFu - (unsigned)bi) << 8 : 0u;
+                        const unsigned whi = wave_umax(chi);
+                        const unsigned wlo = wave_umax(chi == whi ? clo : 0u);
+                        if (!head_max(lbits, whi, wlo, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, true))
+                            goto bail;
+                        if (t == 0 || mdm == dprev) break;     // the guess was the true D_max
+                        dprev = mdm;
                     }
-                    const unsigned chi = best >= 0.0f ? __float_as_uint(best) : 0u;
-                    const unsigned clo = best >= 0.0f ? (0xFFFFFFu - (unsigned)bi) << 8 : 0u;
-                    const unsigned whi = wave_umax(chi);
-                    const unsigned wlo = wave_umax(chi == whi ? clo : 0u);
-                    unsigned mhi, mlo;
-                    if (!head_max(whi, wlo, sh, gslots, a.wgpg, member, seq, mhi, mlo, Kh, D, a.L - 1, true)) goto bail;
                     s = min((int)(0xFFFFFFu - (mlo >> 8)), a.L - 1);   // in range whatever the inputs held
                     sc = __uint_as_float(mhi);
                 }
@@ -388,7 +415,7 @@ size_t resident_select_workspace_bytes(int H, int L, int d)
 {
     Shape s;
     if (!pick_shape(H, L, d, s)) return 0;
-    return round_up((size_t)s.groups * 2 * kMaxMembers * sizeof(unsigned long long), 256) + 256;
+    return round_up((size_t)s.groups * 4 * kMaxMembers * sizeof(unsigned long long), 256) + 256;
 }
 
 hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
@@ -402,7 +429,7 @@ hipError_t launch_select_resident(const void *K, int H, int L, int d, const floa
     a.idx = idx;
     a.score_out = score_out;
     a.slots = reinterpret_cast<unsigned long long *>(ws);
-    const size_t nslots = (size_t)s.groups * 2 * kMaxMembers;
+    const size_t nslots = (size_t)s.groups * 4 * kMaxMembers;
     a.fail = reinterpret_cast<int *>(reinterpret_cast<char *>(ws) + round_up(nslots * sizeof(unsigned long long), 256));
     a.H = H;
     a.L = L;
