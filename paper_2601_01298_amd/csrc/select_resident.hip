@@ -65,6 +65,28 @@ __device__ __forceinline__ unsigned wave_umax(unsigned v)
     return ab > cd ? ab : cd;
 }
 
+// wave-wide float sum; every lane ends up with the same value
+template <int CTRL>
+__device__ __forceinline__ float dpp_fadd(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ float wave_fsum(float v)
+{
+    v = dpp_fadd<0xB1>(v);
+    v = dpp_fadd<0x4E>(v);
+    v = dpp_fadd<0x141>(v);
+    v = dpp_fadd<0x140>(v);
+    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (a + b) + (c + d);
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
 struct Shared {
     unsigned dm[4], hi[4], lo[4];   // one entry per wave of the workgroup
     unsigned rdm, rhi, rlo;         // result of the exchange
@@ -164,6 +186,13 @@ select_resident(ResArgs a)
     constexpr int DW = D / 2;      // 32-bit words per key row
     constexpr int NV = DW / 4;     // 16-byte pieces per key row
     __shared__ uint4 lrows[RLDS > 0 ? RLDS * NV * 256 : 1];
+    __shared__ float nrm[R * 256];     // squared norm of every resident key (private to its thread)
+    constexpr int CAP = (D == 64) ? 48 : 32; // keys the workgroup can stage per step for one-by-one evaluation
+    constexpr int SK = 16;                   // most keys one row slot may stage
+    constexpr int KPP = 64 / DW;             // staged keys evaluated per pass of a wave (a lane per packed pair)
+    __shared__ uint32_t stage[CAP * DW];     // the packed rows of the staged keys
+    __shared__ float sres[CAP];              // their exact squared distances
+    __shared__ int scnt;                     // staging positions handed out this step
     __shared__ Shared sh;
 
     int group, member;
@@ -177,9 +206,16 @@ select_resident(ResArgs a)
     }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = member * 4 + (tid >> 6);
-    if (tid == 0) sh.abort = 0;
+    if (tid == 0) {
+        sh.abort = 0;
+        scnt = 0;
+    }
     __syncthreads();
-    const int rowbase = wv * (R * 64) + lane;          // this lane's r-th key is rowbase + 64 r
+    // Key blocks of 64 are dealt round-robin to the waves of the head: this lane's r-th key is
+    // rowbase + rstride * r.  Neighbouring context positions tend to be neighbours in key space too, so
+    // the keys a new landmark moves would otherwise pile up in one workgroup and make the others wait.
+    const int rowbase = wv * 64 + lane;
+    const int rstride = a.wgpg * 256;
     unsigned long long *gslots = a.slots + (size_t)group * 4 * kMaxMembers;
     const float alpha = a.alpha, oma = 1.0f - a.alpha;
     const float ninf = -__builtin_inff();
@@ -194,7 +230,7 @@ select_resident(ResArgs a)
         uint32_t kr[RREG > 0 ? RREG : 1][DW];
 #pragma unroll
         for (int r = 0; r < RREG; ++r) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(Kh + (size_t)min(rowbase + 64 * r, a.L - 1) * D);
+            const uint4 *p = reinterpret_cast<const uint4 *>(Kh + (size_t)min(rowbase + rstride * r, a.L - 1) * D);
 #pragma unroll
             for (int c = 0; c < NV; ++c) {
                 const uint4 q = p[c];
@@ -206,9 +242,37 @@ select_resident(ResArgs a)
         }
 #pragma unroll
         for (int r = 0; r < RLDS; ++r) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(Kh + (size_t)min(rowbase + 64 * (RREG + r), a.L - 1) * D);
+            const uint4 *p = reinterpret_cast<const uint4 *>(Kh + (size_t)min(rowbase + rstride * (RREG + r), a.L - 1) * D);
 #pragma unroll
             for (int c = 0; c < NV; ++c) lrows[(r * NV + c) * 256 + tid] = p[c];   // private to this thread
+        }
+
+        // ---- squared norms of the resident keys, for the screen below
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float nn = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NV; ++c) {
+                uint32_t w4[4];
+                if (r < RREG) {
+                    w4[0] = kr[r < RREG ? r : 0][4 * c];
+                    w4[1] = kr[r < RREG ? r : 0][4 * c + 1];
+                    w4[2] = kr[r < RREG ? r : 0][4 * c + 2];
+                    w4[3] = kr[r < RREG ? r : 0][4 * c + 3];
+                } else {
+                    const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
+                    w4[0] = q.x;
+                    w4[1] = q.y;
+                    w4[2] = q.z;
+                    w4[3] = q.w;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bf16x2_t pr = __builtin_bit_cast(bf16x2_t, w4[j]);
+                    nn = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, nn, false);
+                }
+            }
+            nrm[r * 256 + tid] = nn;
         }
 
         // ---- u_i = rho_min / rho_i ; keys past L count as already chosen
@@ -217,7 +281,7 @@ select_resident(ResArgs a)
         float rh[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int row = rowbase + 64 * r;
+            const int row = rowbase + rstride * r;
             rh[r] = rhoh[min(row, a.L - 1)];
             if (row < a.L) rmin = fminf(rmin, rh[r]);
         }
@@ -229,7 +293,7 @@ select_resident(ResArgs a)
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const bool live = rowbase + 64 * r < a.L;
+            const bool live = rowbase + rstride * r < a.L;
             Dv[r] = live ? __builtin_inff() : -1.0f;
             ou[r] = live ? oma * (rmin / rh[r]) : ninf;
         }
@@ -241,56 +305,196 @@ select_resident(ResArgs a)
                 unsigned lbits = 0u;
                 if (t > 0) {
                     // ---- distance of every resident key to landmark `prev`
-                    float acc[R];
-#pragma unroll
-                    for (int r = 0; r < R; ++r) acc[r] = 0.0f;
                     // The landmark row is the same for every lane: read it through the constant address
                     // space (K is never written while the kernel runs) so it arrives by scalar loads in
-                    // SGPRs and serves as a broadcast operand instead of occupying 64 VGPRs.
+                    // SGPRs and serves as a broadcast operand instead of occupying VGPRs.
                     typedef const uint32_t __attribute__((address_space(4))) *cptr_t;
                     const cptr_t lp = (cptr_t)(uintptr_t)(Kh + (size_t)prev * D);
-                    // The keys sit in registers as packed bf16 pairs and are widened on the fly each
-                    // step.  Shift count and mask go through an empty asm so the compiler cannot treat
-                    // the widened values as loop-invariant and keep a second, twice as large copy.
+                    // its squared norm: one packed pair per lane, summed over the wave
+                    // (lane l also keeps pair l mod D/2 of the landmark for the one-by-one evaluation below)
+                    const uint32_t lmw = reinterpret_cast<const uint32_t *>(Kh + (size_t)prev * D)[lane % DW];
+                    float nsp = 0.0f;
+                    if (lane < DW) {
+                        const bf16x2_t lw = __builtin_bit_cast(bf16x2_t, lmw);
+                        nsp = __builtin_amdgcn_fdot2_f32_bf16(lw, lw, 0.0f, false);
+                    }
+                    const float ns = wave_fsum(nsp);
+                    const float lm0 = __uint_as_float(lmw << 16), lm1 = __uint_as_float(lmw & 0xFFFF0000u);
+                    const int wvl = tid >> 6;
+                    // Exact evaluation widens the packed bf16 pairs on the fly.  Shift count and mask go
+                    // through an empty asm so the compiler cannot treat the widened values as loop-invariant
+                    // and keep a second, twice as large copy of the keys.
                     unsigned sh16 = 16u, mhi16 = 0xFFFF0000u;
                     asm volatile("" : "+s"(sh16), "+s"(mhi16));
+                    // (a) Screen.  Most keys are far from the new landmark and keep their D.  With
+                    // n = |k|^2, |k_i - s|^2 = n_i + n_s - 2 k_i.s, and the dot product runs on packed bf16
+                    // pairs (v_dot2c_f32_bf16: two elements per instruction, a sixth of the work of
+                    // widening, subtracting and squaring).  Its rounding and cancellation error is below
+                    // 2^-17 (n_i + n_s); a row slot goes on to an exact evaluation unless, for every lane,
+                    // the screened value exceeds D_i^2 by more than 2^-14 (n_i + n_s).  So the screen never
+                    // changes a result: it only skips evaluations that cannot lower D.
+                    // The packed landmark words are pinned in SGPRs for the whole step (the empty asm keeps
+                    // the compiler from re-fetching them in front of every row slot).
+                    uint32_t lws[DW];
 #pragma unroll
-                    for (int c = 0; c < NV; ++c) {
-                        float lm[8];
+                    for (int i = 0; i < DW; ++i) lws[i] = lp[i];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const uint32_t wd = lp[4 * c + j];
-                            lm[2 * j] = __uint_as_float(wd << 16);
-                            lm[2 * j + 1] = __uint_as_float(wd & 0xFFFF0000u);
-                        }
+                    for (int i = 0; i < DW; i += 16)
+                        asm volatile(""
+                                     : "+s"(lws[i]), "+s"(lws[i + 1]), "+s"(lws[i + 2]), "+s"(lws[i + 3]), "+s"(lws[i + 4]),
+                                       "+s"(lws[i + 5]), "+s"(lws[i + 6]), "+s"(lws[i + 7]), "+s"(lws[i + 8]),
+                                       "+s"(lws[i + 9]), "+s"(lws[i + 10]), "+s"(lws[i + 11]), "+s"(lws[i + 12]),
+                                       "+s"(lws[i + 13]), "+s"(lws[i + 14]), "+s"(lws[i + 15]));
+                    // Row slots are screened four at a time so that four independent dot-product chains
+                    // interleave (one chain alone runs at the latency of the instruction, not its rate).
+                    unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
+                    int wtotal = 0;                  // keys of this wave that go to the staging area
 #pragma unroll
-                        for (int r = 0; r < R; ++r) {
-                            uint32_t w4[4];
-                            if (r < RREG) {
-                                w4[0] = kr[r < RREG ? r : 0][4 * c];
-                                w4[1] = kr[r < RREG ? r : 0][4 * c + 1];
-                                w4[2] = kr[r < RREG ? r : 0][4 * c + 2];
-                                w4[3] = kr[r < RREG ? r : 0][4 * c + 3];
-                            } else {
-                                const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
-                                w4[0] = q.x;
-                                w4[1] = q.y;
-                                w4[2] = q.z;
-                                w4[3] = q.w;
+                    for (int g0 = 0; g0 < R; g0 += 4) {
+                        float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                        for (int c = 0; c < NV; ++c) {
+                            uint32_t w4[4][4];
+#pragma unroll
+                            for (int rr = 0; rr < 4; ++rr) {
+                                const int r = g0 + rr;
+                                if (r < RREG) {
+                                    w4[rr][0] = kr[r < RREG ? r : 0][4 * c];
+                                    w4[rr][1] = kr[r < RREG ? r : 0][4 * c + 1];
+                                    w4[rr][2] = kr[r < RREG ? r : 0][4 * c + 2];
+                                    w4[rr][3] = kr[r < RREG ? r : 0][4 * c + 3];
+                                } else if (r < R) {
+                                    const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
+                                    w4[rr][0] = q.x;
+                                    w4[rr][1] = q.y;
+                                    w4[rr][2] = q.z;
+                                    w4[rr][3] = q.w;
+                                } else {
+                                    w4[rr][0] = w4[rr][1] = w4[rr][2] = w4[rr][3] = 0u;
+                                }
                             }
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const float d0 = __uint_as_float(w4[j] << sh16) - lm[2 * j];
-                                acc[r] = fmaf(d0, d0, acc[r]);
-                                const float d1 = __uint_as_float(w4[j] & mhi16) - lm[2 * j + 1];
-                                acc[r] = fmaf(d1, d1, acc[r]);
+                            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                for (int rr = 0; rr < 4; ++rr)
+                                    if (g0 + rr < R)
+                                        dot[rr] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w4[rr][j]),
+                                                                                  __builtin_bit_cast(bf16x2_t, lws[4 * c + j]),
+                                                                                  dot[rr], false);
+                            // rows parked in LDS: one 16-byte piece per row in flight
+                            if (g0 + 3 >= RREG) __builtin_amdgcn_sched_barrier(0);
+                        }
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) {
+                            const int r = g0 + rr;
+                            if (r < R) {
+                                const float nsum = nrm[r * 256 + tid] + ns;
+                                const float d2a = fmaf(-2.0f, dot[rr], nsum);
+                                const bool need = fmaf(nsum, -6.103515625e-5f, d2a) < Dv[r] * Dv[r];
+                                const int cnt = __popcll(__ballot(need));
+                                if (need) needmask |= 1u << r;
+                                if (cnt <= SK) wtotal += cnt;
                             }
                         }
                     }
-                    float lmax = 0.0f;
+                    // one reservation per wave in the workgroup's staging area; if it does not fit (the first
+                    // steps, when most keys move) the wave evaluates whole row slots instead
+                    int base = CAP;
+                    if (wtotal > 0) {
+                        if (lane == 0) base = atomicAdd(&scnt, wtotal);
+                        base = __builtin_amdgcn_readfirstlane(base);
+                    }
+                    const bool fits = base + wtotal <= CAP;
+                    unsigned pm0 = 0u, pm1 = 0u;     // per row slot, 1 + the staging position of this lane's key
+                    float lmax;
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        Dv[r] = fminf(Dv[r], __fsqrt_rn(acc[r]));    // chosen keys stay at -1
+                        const bool need = (needmask >> r) & 1u;
+                        const unsigned long long bal = __ballot(need);
+                        const int cnt = __popcll(bal);
+                        if (cnt > 0 && cnt <= SK && fits) {
+                            // (b) A few keys of the slot may move (the usual case: about 1 % of all keys per
+                            // step): their owners copy the packed rows to the staging area; the 4 waves share
+                            // the staged keys evenly below.
+                            const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32),
+                                                                                  __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+                            base += cnt;
+                            if (need) {
+#pragma unroll
+                                for (int c = 0; c < NV; ++c) {
+                                    uint4 q;
+                                    if (r < RREG) {
+                                        q = make_uint4(kr[r < RREG ? r : 0][4 * c], kr[r < RREG ? r : 0][4 * c + 1],
+                                                       kr[r < RREG ? r : 0][4 * c + 2], kr[r < RREG ? r : 0][4 * c + 3]);
+                                    } else {
+                                        q = lrows[((r - RREG) * NV + c) * 256 + tid];
+                                    }
+                                    *reinterpret_cast<uint4 *>(&stage[pos * DW + 4 * c]) = q;
+                                    if (r >= RREG) __builtin_amdgcn_sched_barrier(0);
+                                }
+                                if (r < 4) pm0 |= (unsigned)(pos + 1) << (8 * (r & 3));
+                                else pm1 |= (unsigned)(pos + 1) << (8 * (r & 3));
+                            }
+                        } else if (cnt > 0) {
+                            // (c) Many keys of the slot may move: the whole slot, each lane its own key,
+                            // direct coordinate differences in fp32.
+                            float acc = 0.0f;
+#pragma unroll
+                            for (int c = 0; c < NV; ++c) {
+                                uint32_t w4[4];
+                                if (r < RREG) {
+                                    w4[0] = kr[r < RREG ? r : 0][4 * c];
+                                    w4[1] = kr[r < RREG ? r : 0][4 * c + 1];
+                                    w4[2] = kr[r < RREG ? r : 0][4 * c + 2];
+                                    w4[3] = kr[r < RREG ? r : 0][4 * c + 3];
+                                } else {
+                                    const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
+                                    w4[0] = q.x;
+                                    w4[1] = q.y;
+                                    w4[2] = q.z;
+                                    w4[3] = q.w;
+                                }
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const uint32_t wd = lws[4 * c + j];
+                                    const float d0 = __uint_as_float(w4[j] << sh16) - __uint_as_float(wd << 16);
+                                    acc = fmaf(d0, d0, acc);
+                                    const float d1 = __uint_as_float(w4[j] & mhi16) - __uint_as_float(wd & 0xFFFF0000u);
+                                    acc = fmaf(d1, d1, acc);
+                                }
+                                if (r >= RREG) __builtin_amdgcn_sched_barrier(0);
+                            }
+                            Dv[r] = fminf(Dv[r], __fsqrt_rn(acc));    // chosen keys stay at -1
+                        }
+                    }
+                    // ---- the staged keys, shared out over the 4 waves: a lane per packed pair (d = 64: two
+                    // keys per pass), direct differences in fp32, summed over the lanes of the group
+                    __syncthreads();
+                    {
+                        const int total = min(scnt, CAP);     // reservations that did not fit left holes: harmless
+                        for (int q0 = wvl * KPP; q0 < total; q0 += 4 * KPP) {
+                            const int kq = min(q0 + lane / DW, CAP - 1);
+                            const uint32_t wd = stage[kq * DW + lane % DW];
+                            const float d0 = __uint_as_float(wd << 16) - lm0;
+                            const float d1 = __uint_as_float(wd & 0xFFFF0000u) - lm1;
+                            float pr = fmaf(d1, d1, d0 * d0);
+                            pr = dpp_fadd<0xB1>(pr);
+                            pr = dpp_fadd<0x4E>(pr);
+                            pr = dpp_fadd<0x141>(pr);
+                            pr = dpp_fadd<0x140>(pr);          // every lane: the sum over its row of 16
+                            const float ot = __shfl_xor(pr, 16);
+                            pr += ot;
+                            if (DW == 64) pr += __shfl_xor(pr, 32);
+                            if (lane % DW == 0) sres[kq] = pr;
+                        }
+                    }
+                    __syncthreads();
+                    if (tid == 0) scnt = 0;      // next use is behind the barriers of the exchange below
+                    lmax = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const unsigned pb = ((r < 4 ? pm0 : pm1) >> (8 * (r & 3))) & 0xFFu;
+                        if (pb) Dv[r] = fminf(Dv[r], __fsqrt_rn(sres[pb - 1]));    // chosen keys stay at -1
                         lmax = fmaxf(lmax, Dv[r]);
                     }
                     lbits = wave_umax(__float_as_uint(lmax));
@@ -317,7 +521,7 @@ select_resident(ResArgs a)
                             const float v = fmaf(ainv, dd, ou[r]);
                             if (v > best) {
                                 best = v;
-                                bi = rowbase + 64 * r;
+                                bi = rowbase + rstride * r;
                             }
                         }
                         const unsigned chi = best >= 0.0f ? __float_as_uint(best) : 0u;
@@ -339,7 +543,7 @@ select_resident(ResArgs a)
                 }
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    if (rowbase + 64 * r == s) {       // chosen: never scored again
+                    if (rowbase + rstride * r == s) {       // chosen: never scored again
                         Dv[r] = -1.0f;
                         ou[r] = ninf;
                     }
