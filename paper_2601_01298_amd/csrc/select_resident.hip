@@ -313,13 +313,6 @@ select_resident(ResArgs a)
                     // its squared norm: one packed pair per lane, summed over the wave
                     // (lane l also keeps pair l mod D/2 of the landmark for the one-by-one evaluation below)
                     const uint32_t lmw = reinterpret_cast<const uint32_t *>(Kh + (size_t)prev * D)[lane % DW];
-                    float nsp = 0.0f;
-                    if (lane < DW) {
-                        const bf16x2_t lw = __builtin_bit_cast(bf16x2_t, lmw);
-                        nsp = __builtin_amdgcn_fdot2_f32_bf16(lw, lw, 0.0f, false);
-                    }
-                    const float ns = wave_fsum(nsp);
-                    const float lm0 = __uint_as_float(lmw << 16), lm1 = __uint_as_float(lmw & 0xFFFF0000u);
                     const int wvl = tid >> 6;
                     // Exact evaluation widens the packed bf16 pairs on the fly.  Shift count and mask go
                     // through an empty asm so the compiler cannot treat the widened values as loop-invariant
@@ -348,7 +341,9 @@ select_resident(ResArgs a)
                     // Row slots are screened four at a time so that four independent dot-product chains
                     // interleave (one chain alone runs at the latency of the instruction, not its rate).
                     unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
+                    unsigned rowmask = 0u;           // bit r: some key of row slot r may move (wave-uniform)
                     int wtotal = 0;                  // keys of this wave that go to the staging area
+                    float ns = 0.0f;                 // squared norm of the landmark (set once its pair has arrived)
 #pragma unroll
                     for (int g0 = 0; g0 < R; g0 += 4) {
                         float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -384,6 +379,16 @@ select_resident(ResArgs a)
                             // rows parked in LDS: one 16-byte piece per row in flight
                             if (g0 + 3 >= RREG) __builtin_amdgcn_sched_barrier(0);
                         }
+                        if (g0 == 0) {
+                            // the landmark's own squared norm: one packed pair per lane, summed over the wave
+                            // (used only now, so the vector load above overlaps the first dot-product chains)
+                            float nsp = 0.0f;
+                            if (lane < DW) {
+                                const bf16x2_t lw = __builtin_bit_cast(bf16x2_t, lmw);
+                                nsp = __builtin_amdgcn_fdot2_f32_bf16(lw, lw, 0.0f, false);
+                            }
+                            ns = wave_fsum(nsp);
+                        }
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) {
                             const int r = g0 + rr;
@@ -393,6 +398,7 @@ select_resident(ResArgs a)
                                 const bool need = fmaf(nsum, -6.103515625e-5f, d2a) < Dv[r] * Dv[r];
                                 const int cnt = __popcll(__ballot(need));
                                 if (need) needmask |= 1u << r;
+                                if (cnt > 0) rowmask |= 1u << r;
                                 if (cnt <= SK) wtotal += cnt;
                             }
                         }
@@ -407,12 +413,16 @@ select_resident(ResArgs a)
                     const bool fits = base + wtotal <= CAP;
                     unsigned pm0 = 0u, pm1 = 0u;     // per row slot, 1 + the staging position of this lane's key
                     float lmax;
+                    unsigned stmask = 0u;            // bit r: row slot r has keys in the staging area (wave-uniform)
+                    rowmask = __builtin_amdgcn_readfirstlane(rowmask);
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
+                        if (!(rowmask & (1u << r))) continue;
                         const bool need = (needmask >> r) & 1u;
                         const unsigned long long bal = __ballot(need);
                         const int cnt = __popcll(bal);
-                        if (cnt > 0 && cnt <= SK && fits) {
+                        if (cnt <= SK && fits) {
+                            stmask |= 1u << r;
                             // (b) A few keys of the slot may move (the usual case: about 1 % of all keys per
                             // step): their owners copy the packed rows to the staging area; the 4 waves share
                             // the staged keys evenly below.
@@ -435,7 +445,7 @@ select_resident(ResArgs a)
                                 if (r < 4) pm0 |= (unsigned)(pos + 1) << (8 * (r & 3));
                                 else pm1 |= (unsigned)(pos + 1) << (8 * (r & 3));
                             }
-                        } else if (cnt > 0) {
+                        } else {
                             // (c) Many keys of the slot may move: the whole slot, each lane its own key,
                             // direct coordinate differences in fp32.
                             float acc = 0.0f;
@@ -472,6 +482,7 @@ select_resident(ResArgs a)
                     __syncthreads();
                     {
                         const int total = min(scnt, CAP);     // reservations that did not fit left holes: harmless
+                        const float lm0 = __uint_as_float(lmw << 16), lm1 = __uint_as_float(lmw & 0xFFFF0000u);
                         for (int q0 = wvl * KPP; q0 < total; q0 += 4 * KPP) {
                             const int kq = min(q0 + lane / DW, CAP - 1);
                             const uint32_t wd = stage[kq * DW + lane % DW];
@@ -482,10 +493,15 @@ select_resident(ResArgs a)
                             pr = dpp_fadd<0x4E>(pr);
                             pr = dpp_fadd<0x141>(pr);
                             pr = dpp_fadd<0x140>(pr);          // every lane: the sum over its row of 16
-                            const float ot = __shfl_xor(pr, 16);
-                            pr += ot;
-                            if (DW == 64) pr += __shfl_xor(pr, 32);
-                            if (lane % DW == 0) sres[kq] = pr;
+                            const float s0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 0));
+                            const float s1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 16));
+                            const float s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 32));
+                            const float s3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 48));
+                            if (DW == 32) {
+                                if (lane < 2) sres[min(q0 + lane, CAP - 1)] = __fsqrt_rn(lane == 0 ? s0 + s1 : s2 + s3);
+                            } else {
+                                if (lane == 0) sres[q0] = __fsqrt_rn((s0 + s1) + (s2 + s3));
+                            }
                         }
                     }
                     __syncthreads();
@@ -493,8 +509,11 @@ select_resident(ResArgs a)
                     lmax = 0.0f;
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        const unsigned pb = ((r < 4 ? pm0 : pm1) >> (8 * (r & 3))) & 0xFFu;
-                        if (pb) Dv[r] = fminf(Dv[r], __fsqrt_rn(sres[pb - 1]));    // chosen keys stay at -1
+                        if (stmask & (1u << r)) {
+                            const unsigned pb = ((r < 4 ? pm0 : pm1) >> (8 * (r & 3))) & 0xFFu;
+                            const float dn = sres[pb ? pb - 1 : 0];
+                            if (pb) Dv[r] = fminf(Dv[r], dn);    // chosen keys stay at -1
+                        }
                         lmax = fmaxf(lmax, Dv[r]);
                     }
                     lbits = wave_umax(__float_as_uint(lmax));
