@@ -116,11 +116,12 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
     }
     __syncthreads();
     if (wave == 0) {
-        const unsigned d4 = lane < 4 ? sh.dm[lane] : 0u;
-        const unsigned h4 = lane < 4 ? sh.hi[lane] : 0u, l4 = lane < 4 ? sh.lo[lane] : 0u;
-        unsigned md = wave_umax(d4);
-        unsigned mh = wave_umax(h4);
-        unsigned ml = wave_umax(h4 == mh ? l4 : 0u);
+        // the 4 waves' entries: every lane reads all of them (same address: a broadcast), no cross-lane step
+        unsigned md = max(max(sh.dm[0], sh.dm[1]), max(sh.dm[2], sh.dm[3]));
+        unsigned mh = max(max(sh.hi[0], sh.hi[1]), max(sh.hi[2], sh.hi[3]));
+        unsigned ml = 0u;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) ml = max(ml, sh.hi[w] == mh ? sh.lo[w] : 0u);
         bool good = true;
         if (nwg > 1) {
             ++seq;
@@ -159,8 +160,20 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
             }
             if (who >= nwg || !good) g = 0ull;
             const unsigned gh = (unsigned)(g >> 32), gl = (unsigned)g & 0xFFFFFF00u;
-            md = wave_umax(kind == 0 ? gh : 0u);
-            mh = wave_umax(kind == 1 ? gh : 0u);
+            // lanes 0..31 hold the D maxima, lanes 32..63 the candidates: one row-wise pass serves both
+            {
+                unsigned v = gh;
+                v = dpp_umax<0xB1>(v);
+                v = dpp_umax<0x4E>(v);
+                v = dpp_umax<0x141>(v);
+                v = dpp_umax<0x140>(v);
+                const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
+                const unsigned r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+                const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
+                const unsigned r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+                md = r0 > r1 ? r0 : r1;
+                mh = r2 > r3 ? r2 : r3;
+            }
             ml = wave_umax((kind == 1 && gh == mh) ? gl : 0u);
             if (touched == 0xFFFFFFFFu && seq == 0u) good = false;   // never true: keeps the touch alive
         }
