@@ -344,6 +344,7 @@ select_resident(ResArgs a)
                     uint32_t lws[DW];
 #pragma unroll
                     for (int i = 0; i < DW; ++i) lws[i] = lp[i];
+                    if (R > 4)      // one group of row slots reads them once anyway
 #pragma unroll
                     for (int i = 0; i < DW; i += 16)
                         asm volatile(""
@@ -493,8 +494,8 @@ select_resident(ResArgs a)
                     // ---- the staged keys, shared out over the 4 waves: a lane per packed pair (d = 64: two
                     // keys per pass), direct differences in fp32, summed over the lanes of the group
                     __syncthreads();
-                    {
-                        const int total = min(scnt, CAP);     // reservations that did not fit left holes: harmless
+                    const int total = min(scnt, CAP);         // reservations that did not fit left holes: harmless
+                    if (total > 0) {                          // the same value in every wave of the workgroup
                         const float lm0 = __uint_as_float(lmw << 16), lm1 = __uint_as_float(lmw & 0xFFFF0000u);
                         for (int q0 = wvl * KPP; q0 < total; q0 += 4 * KPP) {
                             const int kq = min(q0 + lane / DW, CAP - 1);
@@ -516,19 +517,20 @@ select_resident(ResArgs a)
                                 if (lane == 0) sres[q0] = __fsqrt_rn((s0 + s1) + (s2 + s3));
                             }
                         }
+                        __syncthreads();
+                        if (tid == 0) scnt = 0;  // next use is behind the barriers of the exchange below
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            if (stmask & (1u << r)) {
+                                const unsigned pb = ((r < 4 ? pm0 : pm1) >> (8 * (r & 3))) & 0xFFu;
+                                const float dn = sres[pb ? pb - 1 : 0];
+                                if (pb) Dv[r] = fminf(Dv[r], dn);    // chosen keys stay at -1
+                            }
+                        }
                     }
-                    __syncthreads();
-                    if (tid == 0) scnt = 0;      // next use is behind the barriers of the exchange below
                     lmax = 0.0f;
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        if (stmask & (1u << r)) {
-                            const unsigned pb = ((r < 4 ? pm0 : pm1) >> (8 * (r & 3))) & 0xFFu;
-                            const float dn = sres[pb ? pb - 1 : 0];
-                            if (pb) Dv[r] = fminf(Dv[r], dn);    // chosen keys stay at -1
-                        }
-                        lmax = fmaxf(lmax, Dv[r]);
-                    }
+                    for (int r = 0; r < R; ++r) lmax = fmaxf(lmax, Dv[r]);
                     lbits = wave_umax(__float_as_uint(lmax));
                 }
 
