@@ -6,8 +6,15 @@
 // and LDS of the chip together hold ~100 MB, so a few dozen heads at a time fit ON CHIP.  Here
 // every wave owns 64*R keys for the whole life of a head: lane l keeps R complete key rows
 // (RREG of them in VGPRs, RLDS in a private strip of LDS), its D and u values, and never
-// touches HBM again until the next head.  The landmark row is fetched once per step through
-// the scalar cache into SGPRs and used as a broadcast operand.
+// touches HBM again until the next head.  Blocks of 64 keys are dealt round-robin to the waves of
+// the head.  The landmark row is fetched once per step through the scalar cache into SGPRs and
+// used as a broadcast operand.
+//
+// Only about 1 % of the keys get closer to the chosen set in a step.  A dot-product screen on the
+// packed bf16 pairs (|k-s|^2 = |k|^2 + |s|^2 - 2 k.s, v_dot2c_f32_bf16) with a proven error margin
+// finds the keys that cannot move; the rest are evaluated exactly, by direct differences in fp32:
+// their rows go to a staging area of the workgroup and the 4 waves share them evenly, a lane per
+// packed pair.  The screen only skips work, it never decides a value.
 //
 // A head is shared by up to 32 workgroups of 4 waves, placed on one accelerator die.  A step needs
 // two maxima over all keys of the head, the second depending on the first: D_max, then the best
