@@ -210,6 +210,60 @@ def test_select_edge_cases(ws, oracle, select_kernel):
     assert one.cpu().numpy().tolist() == [[0]]
 
 
+def test_select_edge_cases_bf16(ws, oracle, select_kernel):
+    """The same degenerate cases on bf16 keys, which the on-chip kernel serves: k = L with duplicates (the
+    covering radius ends at zero), exact ties, heads shorter than one block of keys, k = 1."""
+    import torch
+    rng = np.random.default_rng(10)
+    K = syn.round_to_bf16(rng.standard_normal((2, 200, 64)).astype(np.float32))
+    K[0, 150] = K[0, 7]
+    K[0, 151] = K[0, 7]
+    K[1, 199] = K[1, 0]
+    Kd = to_device(K, "bf16")
+    sig = [float(syn.bandwidth(K[h])) for h in range(2)]
+    rho = ws.ws_synapse_density(Kd, sig)
+    for alpha in (0.5, 1.0):
+        idx = ws.ws_synapse_select(Kd, rho, 200, alpha).cpu().numpy()
+        for h in range(2):
+            rho_ref = oracle.density(K[h], sig[h])
+            ref, _, gap = oracle.select(K[h], rho_ref, 200, alpha)
+            assert sorted(idx[h].tolist()) == list(range(200))
+            forks = check_indices(oracle, K[h], rho_ref, 200, alpha, idx[h], ref)
+            print(f"bf16 k=L alpha={alpha} head {h}: forks {forks}, steps below tie tolerance {(gap < TIE_TOL).sum()}")
+    P = np.zeros((3, 5, 64), dtype=np.float32)
+    P[:, :, 0] = [0, 3, 7, 10, 5]
+    idx = ws.ws_synapse_select(to_device(P, "bf16"), torch.ones((3, 5), device="cuda"), 5, 1.0).cpu().numpy()
+    assert idx.tolist() == [[0, 3, 4, 1, 2]] * 3
+    one = ws.ws_synapse_select(Kd[:, :1].contiguous(), torch.ones((2, 1), device="cuda"), 1, 0.5)
+    assert one.cpu().numpy().tolist() == [[0], [0]]
+
+
+def test_select_is_repeatable_and_reuses_its_workspace(ws, oracle, select_kernel):
+    """The selection kernels are persistent and their workgroups talk through tagged slots in the workspace:
+    the same call repeated on one workspace (never cleared by the caller, a different k in between) must give
+    the same indices bit for bit, with more heads than are in flight at once."""
+    import torch
+    w = variant(2, H=72, Hq=72, L=2048, k=41)
+    K = np.stack([syn.cloud(w, h % 6, syn.TENSOR_K) for h in range(w.H)])
+    Kd = to_device(K, w.dtype)
+    sigma = [float(syn.bandwidth(K[h])) for h in range(w.H)]
+    rho = ws.ws_synapse_density(Kd, sigma)
+    need = ws.ws_synapse_workspace_bytes(ws.WS_OP_SELECT, ws.WS_BF16, w.H, w.L, w.d, w.k)
+    wsb = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda")      # garbage, on purpose
+    first = ws.ws_synapse_select(Kd, rho, w.k, w.alpha, workspace=wsb).cpu().numpy()
+    assert (first >= 0).all()
+    for h in range(6, w.H):
+        assert np.array_equal(first[h], first[h % 6])                      # copies of a head pick the same keys
+    ws.ws_synapse_select(Kd, rho, 7, 1.0, workspace=wsb)
+    for _ in range(8):
+        again = ws.ws_synapse_select(Kd, rho, w.k, w.alpha, workspace=wsb).cpu().numpy()
+        assert np.array_equal(again, first)
+    for h in range(6):
+        rho_ref = oracle.density(K[h], sigma[h])
+        ref, _, _ = oracle.select(K[h], rho_ref, w.k, w.alpha)
+        check_indices(oracle, K[h], rho_ref, w.k, w.alpha, first[h], ref)
+
+
 # --------------------------------------------------------------------------------- gather
 @pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 128), ("f32", 64)])
 def test_gather_is_bit_exact(ws, oracle, dtype, d):
