@@ -13,8 +13,9 @@
 // Only about 1 % of the keys get closer to the chosen set in a step.  A dot-product screen on the
 // packed bf16 pairs (|k-s|^2 = |k|^2 + |s|^2 - 2 k.s, v_dot2c_f32_bf16) with a proven error margin
 // finds the keys that cannot move; the rest are evaluated exactly, by direct differences in fp32:
-// their rows go to a staging area of the workgroup and the 4 waves share them evenly, a lane per
-// packed pair.  The screen only skips work, it never decides a value.
+// their owners copy the rows to a staging strip of the wave, which then evaluates them one by one
+// (d = 64: two at a time), a lane per packed pair.  The screen only skips work, it never decides a
+// value.
 //
 // A head is shared by up to 32 workgroups of 4 waves, placed on one accelerator die.  A step needs
 // two maxima over all keys of the head, the second depending on the first: D_max, then the best
@@ -207,12 +208,11 @@ select_resident(ResArgs a)
     constexpr int NV = DW / 4;     // 16-byte pieces per key row
     __shared__ uint4 lrows[RLDS > 0 ? RLDS * NV * 256 : 1];
     __shared__ float nrm[R * 256];     // squared norm of every resident key (private to its thread)
-    constexpr int CAP = (D == 64) ? 48 : 32; // keys the workgroup can stage per step for one-by-one evaluation
-    constexpr int SK = 16;                   // most keys one row slot may stage
+    constexpr int CAP = (D == 64) ? 12 : 8;  // keys a wave can stage per step for one-by-one evaluation
+    constexpr int SK = CAP;                  // most keys one row slot may stage
     constexpr int KPP = 64 / DW;             // staged keys evaluated per pass of a wave (a lane per packed pair)
-    __shared__ uint32_t stage[CAP * DW];     // the packed rows of the staged keys
-    __shared__ float sres[CAP];              // their exact squared distances
-    __shared__ int scnt;                     // staging positions handed out this step
+    __shared__ uint32_t stage_all[4][CAP * DW];   // per wave: the packed rows of the staged keys
+    __shared__ float sres_all[4][CAP];            // per wave: their exact distances
     __shared__ Shared sh;
 
     int group, member;
@@ -226,10 +226,7 @@ select_resident(ResArgs a)
     }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = member * 4 + (tid >> 6);
-    if (tid == 0) {
-        sh.abort = 0;
-        scnt = 0;
-    }
+    if (tid == 0) sh.abort = 0;
     __syncthreads();
     // Key blocks of 64 are dealt round-robin to the waves of the head: this lane's r-th key is
     // rowbase + rstride * r.  Neighbouring context positions tend to be neighbours in key space too, so
@@ -424,14 +421,12 @@ select_resident(ResArgs a)
                             }
                         }
                     }
-                    // one reservation per wave in the workgroup's staging area; if it does not fit (the first
-                    // steps, when most keys move) the wave evaluates whole row slots instead
-                    int base = CAP;
-                    if (wtotal > 0) {
-                        if (lane == 0) base = atomicAdd(&scnt, wtotal);
-                        base = __builtin_amdgcn_readfirstlane(base);
-                    }
-                    const bool fits = base + wtotal <= CAP;
+                    // if the wave's keys do not fit its staging strip (the first steps, when most keys move) it
+                    // evaluates whole row slots instead
+                    int base = 0;
+                    const bool fits = wtotal <= CAP;
+                    uint32_t *stage = stage_all[wvl];
+                    float *sres = sres_all[wvl];
                     unsigned pm0 = 0u, pm1 = 0u;     // per row slot, 1 + the staging position of this lane's key
                     float lmax;
                     unsigned stmask = 0u;            // bit r: row slot r has keys in the staging area (wave-uniform)
@@ -445,8 +440,7 @@ select_resident(ResArgs a)
                         if (cnt <= SK && fits) {
                             stmask |= 1u << r;
                             // (b) A few keys of the slot may move (the usual case: about 1 % of all keys per
-                            // step): their owners copy the packed rows to the staging area; the 4 waves share
-                            // the staged keys evenly below.
+                            // step): their owners copy the packed rows to the wave's staging strip.
                             const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32),
                                                                                   __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
                             base += cnt;
@@ -498,13 +492,16 @@ select_resident(ResArgs a)
                             Dv[r] = fminf(Dv[r], __fsqrt_rn(acc));    // chosen keys stay at -1
                         }
                     }
-                    // ---- the staged keys, shared out over the 4 waves: a lane per packed pair (d = 64: two
-                    // keys per pass), direct differences in fp32, summed over the lanes of the group
-                    __syncthreads();
-                    const int total = min(scnt, CAP);         // reservations that did not fit left holes: harmless
-                    if (total > 0) {                          // the same value in every wave of the workgroup
+                    // ---- the staged keys of this wave: a lane per packed pair (d = 64: two keys per pass),
+                    // direct differences in fp32, summed over the lanes of the group (DPP, then readlane);
+                    // no barrier and no atomic: since key blocks are dealt round-robin the waves of a head
+                    // stage about the same number of keys
+                    const int total = fits ? wtotal : 0;
+                    if (total > 0) {
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
                         const float lm0 = __uint_as_float(lmw << 16), lm1 = __uint_as_float(lmw & 0xFFFF0000u);
-                        for (int q0 = wvl * KPP; q0 < total; q0 += 4 * KPP) {
+                        for (int q0 = 0; q0 < total; q0 += KPP) {
                             const int kq = min(q0 + lane / DW, CAP - 1);
                             const uint32_t wd = stage[kq * DW + lane % DW];
                             const float d0 = __uint_as_float(wd << 16) - lm0;
@@ -524,8 +521,8 @@ select_resident(ResArgs a)
                                 if (lane == 0) sres[q0] = __fsqrt_rn((s0 + s1) + (s2 + s3));
                             }
                         }
-                        __syncthreads();
-                        if (tid == 0) scnt = 0;  // next use is behind the barriers of the exchange below
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
 #pragma unroll
                         for (int r = 0; r < R; ++r) {
                             if (stmask & (1u << r)) {
