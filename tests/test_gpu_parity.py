@@ -238,6 +238,32 @@ def test_select_edge_cases_bf16(ws, oracle, select_kernel):
     assert one.cpu().numpy().tolist() == [[0], [0]]
 
 
+@pytest.mark.parametrize("cfg,H,L,k,rows", [(2, 40, 4096, 30, "2 rows per lane"), (2, 96, 4096, 30, "4 rows per lane"),
+                                            (2, 136, 4096, 30, "6 + 2 rows per lane"), (4, 40, 4096, 30, "d=128, 2 rows"),
+                                            (4, 72, 4096, 30, "d=128, 3 + 1 rows")])
+def test_select_resident_every_instance(ws, oracle, monkeypatch, cfg, H, L, k, rows):
+    """The on-chip kernel is compiled for several splits of a head (key rows per lane in registers + in
+    LDS); the library takes the one with the fewest passes over the heads.  These head counts make it take
+    each split in turn (with L = 4096: 16, 8, 4 or 2 workgroups per head).  Heads are copies of 4 clouds:
+    the 4 are checked against the oracle, the copies against them."""
+    monkeypatch.delenv("WS_SYNAPSE_SELECT", raising=False)
+    w = variant(cfg, H=H, Hq=H, L=L, k=k)
+    base = [syn.cloud(w, h, syn.TENSOR_K) for h in range(4)]
+    K = np.stack([base[h % 4] for h in range(H)])
+    sigma = [float(syn.bandwidth(base[h % 4])) for h in range(H)]
+    Kd = to_device(K, w.dtype)
+    assert ws.ws_synapse_select_is_resident(ws.WS_BF16, H, L, w.d)
+    rho = ws.ws_synapse_density(Kd, sigma)
+    idx = ws.ws_synapse_select(Kd, rho, k, w.alpha).cpu().numpy()
+    for h in range(4, H):
+        assert np.array_equal(idx[h], idx[h % 4]), f"head {h} differs from its original"
+    for h in range(4):
+        rho_ref = oracle.density(base[h], sigma[h])
+        ref, _, gap = oracle.select(base[h], rho_ref, k, w.alpha)
+        forks = check_indices(oracle, base[h], rho_ref, k, w.alpha, idx[h], ref)
+        print(f"{rows}: head {h} forks {forks}, steps below tie tolerance {(gap < TIE_TOL).sum()}")
+
+
 def test_select_is_repeatable_and_reuses_its_workspace(ws, oracle, select_kernel):
     """The selection kernels are persistent and their workgroups talk through tagged slots in the workspace:
     the same call repeated on one workspace (never cleared by the caller, a different k in between) must give
