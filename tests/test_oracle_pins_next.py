@@ -2,10 +2,24 @@
 proxy, validation gate, RoPE rotation of injected rows) against closed forms, library routines and
 invariants -- never against the oracle's own formula retyped."""
 import math
+import os
 
 import numpy as np
 import pytest
 from scipy.special import softmax
+
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "closed_forms.txt")
+
+
+def golden(name):
+    for line in open(GOLD):
+        if line.startswith("#") or "|" not in line:
+            continue
+        key, vals, _ = [p.strip() for p in line.split("|", 2)]
+        if key == name:
+            return np.array([float(v) for v in vals.split()])
+    raise KeyError(name)
 
 
 def rng_arr(seed, *shape):
@@ -16,7 +30,7 @@ def rng_arr(seed, *shape):
 def test_mass_two_token_closed_form(oracle):
     # one head, d = 1: logits (0, ln 3) -> softmax (1/4, 3/4)
     A = oracle.attention_mass(np.array([[[0.0], [1.0]]]), np.array([[math.log(3.0)]]), scale=1.0)
-    assert np.allclose(A, [0.25, 0.75], rtol=1e-15)
+    assert np.allclose(A, golden("mass_two_tokens"), rtol=1e-15)
     # default scale is 1/sqrt(d): d = 4, q.k = 2 ln 3 -> same logits after scaling
     K = np.zeros((1, 2, 4))
     K[0, 1, :] = 1.0
@@ -78,7 +92,7 @@ def test_gate_hand_values(oracle):
     h = np.array([1.0, 0.0])
     T = np.array([[3.0, 4.0], [1.0, 2.0], [-2.0, 0.0], [0.0, 5.0], [0.0, 0.0], [7.0, 0.0]])
     score, acc = oracle.gate(h, T, 0.5)
-    assert np.allclose(score, [0.6, 1 / math.sqrt(5), -1.0, 0.0, 0.0, 1.0], rtol=1e-15, atol=1e-300)
+    assert np.allclose(score, golden("gate_cosines"), rtol=1e-15, atol=1e-300)
     assert list(acc) == [1, 0, 0, 0, 0, 1]
     # the threshold itself passes (only score < theta is rejected)
     _, acc = oracle.gate(h, T[:1], 0.6)
@@ -109,6 +123,7 @@ def test_rope_hand_values(oracle):
     x = np.array([[0.0, 1.0, 0.0, 0.0]])
     y = oracle.rope(x, [7], base=100.0)
     assert np.allclose(y, [[0.0, math.cos(0.7), 0.0, math.sin(0.7)]], rtol=1e-14, atol=1e-300)
+    assert np.allclose(y[0], golden("rope_d4_base100"), rtol=1e-14, atol=1e-300)
     x = np.array([[2.0, 0.0, 0.0, 0.0]])
     y = oracle.rope(x, [3], base=100.0)
     assert np.allclose(y, [[2 * math.cos(3), 0.0, 2 * math.sin(3), 0.0]], rtol=1e-14, atol=1e-300)
