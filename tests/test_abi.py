@@ -130,3 +130,22 @@ def test_bad_arguments_of_the_next_steps_are_rejected_on_the_host(lib):
     assert b.ws_synapse_workspace_bytes(b.WS_OP_INJECT, b.WS_BF16, 2, 100, 64, k=3) >= 3 * 32 * 8
     assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTENTION_MASS, b.WS_BF16, 8, 4096, 64, Hq=8) >= 8 * 4096 * 4
     assert b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY_APPEND, b.WS_BF16, 8, 4096, 64) > 0
+
+
+def test_selection_kernel_choice_is_host_logic(lib, monkeypatch):
+    """Which selection kernel a shape gets is decided on the host from the sizes alone: heads whose keys fit
+    the chip's registers and LDS (32 headline heads at a time) stay on chip, fp32 keys and oversized heads stream."""
+    from paper_2601_01298_amd import binding as b
+    from paper_2601_01298_amd import synthetic as syn
+    monkeypatch.delenv("WS_SYNAPSE_SELECT", raising=False)
+    expect = {1: False, 2: True, 3: True, 4: True, 5: False}
+    for cfg, w in syn.WORKLOADS.items():
+        dt = b.WS_BF16 if w.dtype == "bf16" else b.WS_F32
+        assert b.ws_synapse_select_is_resident(dt, w.H, w.L, w.d) == expect[cfg], w.name
+        assert b.ws_synapse_workspace_bytes(b.WS_OP_SELECT, dt, w.H, w.L, w.d, w.k) > 0
+    monkeypatch.setenv("WS_SYNAPSE_SELECT", "stream")
+    assert not b.ws_synapse_select_is_resident(b.WS_BF16, 384, 32768, 64)
+    # the density workspace grows with the number of heads only up to one chunk of column partial sums
+    a = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 128, 32768, 64)
+    c = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 384, 32768, 64)
+    assert c - a == 256 * 32768 * 16 + 256 * 4      # 16-byte record per key + exponent scale per head
