@@ -453,7 +453,10 @@ density_finish(const float *__restrict__ rowsum, const float *__restrict__ colpa
     rho[(size_t)(head0 + hl) * L + i] = t / (float)L;
 }
 
-constexpr int kSymChunkHeads = 128;     // heads per symmetric launch (bounds the partial-sum workspace)
+// Heads go through the symmetric sweep in as few launches as the column partial sums allow: their
+// workspace (heads x slots x keys x 4 bytes) is kept under 4 GiB, and a launch takes at most 1024 heads.
+constexpr size_t kSymPartialBytes = (size_t)4 << 30;
+constexpr int kSymChunkHeads = 1024;
 
 constexpr int kSymRtw64 = 2, kSymRtw128 = 2;   // row tiles per wave
 static inline int sym_bm(int d) { return 128 * (d == 64 ? kSymRtw64 : kSymRtw128); }
@@ -478,7 +481,11 @@ static DensityWs density_layout(int H, int L, int d, bool bf16)
     if (use_sym(bf16, L, d)) {
         w.nB = w.Lpad / sym_bm(d);
         w.nBoth = (w.nB - 1) / 2;
-        w.chunk = H < kSymChunkHeads ? H : kSymChunkHeads;
+        const size_t per_head = (size_t)w.nBoth * w.Lpad * sizeof(float);
+        size_t fit = per_head ? kSymPartialBytes / per_head : (size_t)kSymChunkHeads;
+        if (fit < 1) fit = 1;
+        if (fit > (size_t)kSymChunkHeads) fit = kSymChunkHeads;
+        w.chunk = (size_t)H < fit ? H : (int)fit;
         w.colpart = w.rowsum + round_up((size_t)w.chunk * w.Lpad * sizeof(float), 256);
         w.total = w.colpart + round_up((size_t)w.chunk * w.nBoth * w.Lpad * sizeof(float), 256);
     }
