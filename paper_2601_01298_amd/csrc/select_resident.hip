@@ -208,11 +208,13 @@ select_resident(ResArgs a)
     constexpr int NV = DW / 4;     // 16-byte pieces per key row
     __shared__ uint4 lrows[RLDS > 0 ? RLDS * NV * 256 : 1];
     __shared__ float nrm[R * 256];     // squared norm of every resident key (private to its thread)
-    constexpr int CAP = (D == 64) ? 12 : 8;  // keys a wave can stage per step for one-by-one evaluation
+    constexpr int LPK = DW / 2;              // lanes that share one staged key: 2 packed words (4 elements) each
+    constexpr int KPP = 64 / LPK;            // staged keys a wave evaluates per pass (d = 64: four, d = 128: two)
+    constexpr int CAP = (D == 64) ? 12 : 8;  // keys a wave can stage per step
     constexpr int SK = CAP;                  // most keys one row slot may stage
-    constexpr int KPP = 64 / DW;             // staged keys evaluated per pass of a wave (a lane per packed pair)
-    __shared__ uint32_t stage_all[4][CAP * DW];   // per wave: the packed rows of the staged keys
-    __shared__ float sres_all[4][CAP];            // per wave: their exact distances
+    static_assert(CAP % KPP == 0, "whole passes");
+    __shared__ __align__(16) uint32_t stage_all[4][CAP * DW];   // per wave: the packed rows of the staged keys
+    __shared__ float sres_all[4][CAP];                          // per wave: the staged keys' exact distances
     __shared__ Shared sh;
 
     int group, member;
@@ -358,26 +360,47 @@ select_resident(ResArgs a)
                                        "+s"(lws[i + 13]), "+s"(lws[i + 14]), "+s"(lws[i + 15]));
                     // Row slots are screened four at a time so that four independent dot-product chains
                     // interleave (one chain alone runs at the latency of the instruction, not its rate).
+                    // With rows parked in LDS a group is three register rows and one LDS row, whose 16-byte
+                    // pieces are read two pieces ahead of their use: the LDS latency hides behind the
+                    // dot products of two pieces instead of stalling every piece.
                     unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
                     unsigned rowmask = 0u;           // bit r: some key of row slot r may move (wave-uniform)
                     int wtotal = 0;                  // keys of this wave that go to the staging area
                     float ns = 0.0f;                 // squared norm of the landmark (set once its pair has arrived)
+                    constexpr bool MIX = RLDS > 0;   // groups of 3 + 1
+                    constexpr int NG = MIX ? RLDS : (R + 3) / 4;
+                    static_assert(!MIX || (RREG == 3 * RLDS), "a group is three register rows and one LDS row");
 #pragma unroll
-                    for (int g0 = 0; g0 < R; g0 += 4) {
+                    for (int g = 0; g < NG; ++g) {
+                        // row slot behind position rr of this group (-1: none)
+                        auto rowof = [&](int rr) -> int {
+                            if (MIX) return rr < 3 ? 3 * g + rr : RREG + g;
+                            return 4 * g + rr < R ? 4 * g + rr : -1;
+                        };
                         float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        uint4 pf[3];                 // LDS row: pieces c, c+1, c+2 in flight
+                        if (MIX) {
+                            pf[0] = lrows[(g * NV + 0) * 256 + tid];
+                            pf[1] = lrows[(g * NV + 1) * 256 + tid];
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
 #pragma unroll
                         for (int c = 0; c < NV; ++c) {
+                            if (MIX) {
+                                if (c + 2 < NV) pf[(c + 2) % 3] = lrows[(g * NV + c + 2) * 256 + tid];
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
                             uint32_t w4[4][4];
 #pragma unroll
                             for (int rr = 0; rr < 4; ++rr) {
-                                const int r = g0 + rr;
-                                if (r < RREG) {
-                                    w4[rr][0] = kr[r < RREG ? r : 0][4 * c];
-                                    w4[rr][1] = kr[r < RREG ? r : 0][4 * c + 1];
-                                    w4[rr][2] = kr[r < RREG ? r : 0][4 * c + 2];
-                                    w4[rr][3] = kr[r < RREG ? r : 0][4 * c + 3];
-                                } else if (r < R) {
-                                    const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
+                                const int r = rowof(rr);
+                                if (r >= 0 && r < RREG) {
+                                    w4[rr][0] = kr[r >= 0 && r < RREG ? r : 0][4 * c];
+                                    w4[rr][1] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 1];
+                                    w4[rr][2] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 2];
+                                    w4[rr][3] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 3];
+                                } else if (r >= 0) {
+                                    const uint4 q = pf[c % 3];
                                     w4[rr][0] = q.x;
                                     w4[rr][1] = q.y;
                                     w4[rr][2] = q.z;
@@ -390,14 +413,13 @@ select_resident(ResArgs a)
                             for (int j = 0; j < 4; ++j)
 #pragma unroll
                                 for (int rr = 0; rr < 4; ++rr)
-                                    if (g0 + rr < R)
+                                    if (rowof(rr) >= 0)
                                         dot[rr] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w4[rr][j]),
                                                                                   __builtin_bit_cast(bf16x2_t, lws[4 * c + j]),
                                                                                   dot[rr], false);
-                            // rows parked in LDS: one 16-byte piece per row in flight
-                            if (g0 + 3 >= RREG) __builtin_amdgcn_sched_barrier(0);
+                            if (MIX) __builtin_amdgcn_sched_barrier(0);
                         }
-                        if (g0 == 0) {
+                        if (g == 0) {
                             // the landmark's own squared norm: one packed pair per lane, summed over the wave
                             // (used only now, so the vector load above overlaps the first dot-product chains)
                             float nsp = 0.0f;
@@ -409,8 +431,8 @@ select_resident(ResArgs a)
                         }
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) {
-                            const int r = g0 + rr;
-                            if (r < R) {
+                            const int r = rowof(rr);
+                            if (r >= 0) {
                                 const float nsum = nrm[r * 256 + tid] + ns;
                                 const float d2a = fmaf(-2.0f, dot[rr], nsum);
                                 const bool need = fmaf(nsum, -6.103515625e-5f, d2a) < Dv[r] * Dv[r];
@@ -492,33 +514,44 @@ select_resident(ResArgs a)
                             Dv[r] = fminf(Dv[r], __fsqrt_rn(acc));    // chosen keys stay at -1
                         }
                     }
-                    // ---- the staged keys of this wave: a lane per packed pair (d = 64: two keys per pass),
-                    // direct differences in fp32, summed over the lanes of the group (DPP, then readlane);
-                    // no barrier and no atomic: since key blocks are dealt round-robin the waves of a head
-                    // stage about the same number of keys
+                    // ---- the staged keys of this wave, KPP per pass: LPK lanes share a key, each takes two
+                    // packed words of it and of the landmark row (both from LDS), direct differences in fp32,
+                    // then the partial sums of a key meet by DPP inside their lane group.  No barrier and no
+                    // atomic: since key blocks are dealt round-robin the waves of a head stage about the same
+                    // number of keys.
                     const int total = fits ? wtotal : 0;
                     if (total > 0) {
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
-                        const float lm0 = __uint_as_float(lmw << 16), lm1 = __uint_as_float(lmw & 0xFFFF0000u);
-                        for (int q0 = 0; q0 < total; q0 += KPP) {
-                            const int kq = min(q0 + lane / DW, CAP - 1);
-                            const uint32_t wd = stage[kq * DW + lane % DW];
-                            const float d0 = __uint_as_float(wd << 16) - lm0;
-                            const float d1 = __uint_as_float(wd & 0xFFFF0000u) - lm1;
-                            float pr = fmaf(d1, d1, d0 * d0);
+                        // lane-derived addresses are rebuilt here every step: hoisted out of the step loop they would
+                        // occupy registers that the resident keys need
+                        int ln = lane;
+                        asm volatile("" : "+v"(ln));
+                        // a lane takes packed words `part` and `part + LPK` of its key; of the landmark row it holds
+                        // one of the two already (lmw), the lane LPK further on holds the other
+                        const int sub = ln / LPK, part = ln % LPK;
+                        const uint32_t other = (uint32_t)__shfl_xor((int)lmw, LPK);
+                        const bool odd = (sub & 1) != 0;
+                        const uint32_t wa = odd ? other : lmw, wb = odd ? lmw : other;
+                        const float l0 = __uint_as_float(wa << 16), l1 = __uint_as_float(wa & 0xFFFF0000u);
+                        const float l2 = __uint_as_float(wb << 16), l3 = __uint_as_float(wb & 0xFFFF0000u);
+                        for (int q0 = 0; q0 < total; q0 += KPP) {        // slots past `total` hold stale rows: computed, never used
+                            const uint32_t ka = stage[(q0 + sub) * DW + part], kb = stage[(q0 + sub) * DW + part + LPK];
+                            const float d0 = __uint_as_float(ka << 16) - l0, d1 = __uint_as_float(ka & 0xFFFF0000u) - l1;
+                            const float d2 = __uint_as_float(kb << 16) - l2, d3 = __uint_as_float(kb & 0xFFFF0000u) - l3;
+                            float pr = fmaf(d1, d1, d0 * d0) + fmaf(d3, d3, d2 * d2);
                             pr = dpp_fadd<0xB1>(pr);
                             pr = dpp_fadd<0x4E>(pr);
                             pr = dpp_fadd<0x141>(pr);
                             pr = dpp_fadd<0x140>(pr);          // every lane: the sum over its row of 16
-                            const float s0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 0));
-                            const float s1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 16));
-                            const float s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 32));
-                            const float s3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 48));
-                            if (DW == 32) {
-                                if (lane < 2) sres[min(q0 + lane, CAP - 1)] = __fsqrt_rn(lane == 0 ? s0 + s1 : s2 + s3);
+                            if (LPK == 16) {
+                                if (part == 0) sres[q0 + sub] = __fsqrt_rn(pr);
                             } else {
-                                if (lane == 0) sres[q0] = __fsqrt_rn((s0 + s1) + (s2 + s3));
+                                const float s0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 0));
+                                const float s1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 16));
+                                const float s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 32));
+                                const float s3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 48));
+                                if (ln < 2) sres[q0 + ln] = __fsqrt_rn(ln == 0 ? s0 + s1 : s2 + s3);
                             }
                         }
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
