@@ -95,6 +95,15 @@ __device__ __forceinline__ float wave_fsum(float v)
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
+// Second half of a 64-bit maximum over the wave: `lo` of the lane whose first half matched.  Nearly
+// always exactly one lane matches, and then a ballot and one readlane replace the whole reduction.
+__device__ __forceinline__ unsigned wave_pick_lo(bool match, unsigned lo)
+{
+    const unsigned long long m = __ballot(match);
+    if (__popcll(m) == 1) return (unsigned)__builtin_amdgcn_readlane((int)lo, (int)__builtin_ctzll(m));
+    return wave_umax(match ? lo : 0u);
+}
+
 struct Shared {
     unsigned dm[4], hi[4], lo[4];   // one entry per wave of the workgroup
     unsigned rdm, rhi, rlo;         // result of the exchange
@@ -182,7 +191,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
                 md = r0 > r1 ? r0 : r1;
                 mh = r2 > r3 ? r2 : r3;
             }
-            ml = wave_umax((kind == 1 && gh == mh) ? gl : 0u);
+            ml = wave_pick_lo(kind == 1 && gh == mh, gl);
             if (touched == 0xFFFFFFFFu && seq == 0u) good = false;   // never true: keeps the touch alive
         }
         if (lane == 0) {
@@ -598,7 +607,7 @@ select_resident(ResArgs a)
                         const unsigned chi = best >= 0.0f ? __float_as_uint(best) : 0u;
                         const unsigned clo = best >= 0.0f ? (0xFFFFFFu - (unsigned)bi) << 8 : 0u;
                         const unsigned whi = wave_umax(chi);
-                        const unsigned wlo = wave_umax(chi == whi ? clo : 0u);
+                        const unsigned wlo = wave_pick_lo(chi == whi, clo);
                         if (!head_max(lbits, whi, wlo, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, true))
                             goto bail;
                         if (t == 0 || mdm == dprev) break;     // the guess was the true D_max
