@@ -220,7 +220,6 @@ select_resident(ResArgs a)
     constexpr int LPK = DW / 2;              // lanes that share one staged key: 2 packed words (4 elements) each
     constexpr int KPP = 64 / LPK;            // staged keys a wave evaluates per pass (d = 64: four, d = 128: two)
     constexpr int CAP = (D == 64) ? 12 : 8;  // keys a wave can stage per step
-    constexpr int SK = CAP;                  // most keys one row slot may stage
     static_assert(CAP % KPP == 0, "whole passes");
     __shared__ __align__(16) uint32_t stage_all[4][CAP * DW];   // per wave: the packed rows of the staged keys
     __shared__ float sres_all[4][CAP];                          // per wave: the staged keys' exact distances
@@ -374,7 +373,6 @@ select_resident(ResArgs a)
                     // dot products of two pieces instead of stalling every piece.
                     unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
                     unsigned rowmask = 0u;           // bit r: some key of row slot r may move (wave-uniform)
-                    int wtotal = 0;                  // keys of this wave that go to the staging area
                     float ns = 0.0f;                 // squared norm of the landmark (set once its pair has arrived)
                     constexpr bool MIX = RLDS > 0;   // groups of 3 + 1
                     constexpr int NG = MIX ? RLDS : (R + 3) / 4;
@@ -448,14 +446,12 @@ select_resident(ResArgs a)
                                 const int cnt = __popcll(__ballot(need));
                                 if (need) needmask |= 1u << r;
                                 if (cnt > 0) rowmask |= 1u << r;
-                                if (cnt <= SK) wtotal += cnt;
                             }
                         }
                     }
-                    // if the wave's keys do not fit its staging strip (the first steps, when most keys move) it
-                    // evaluates whole row slots instead
+                    // row slots whose keys no longer fit the wave's staging strip (the first steps, when most keys
+                    // move) are evaluated whole instead
                     int base = 0;
-                    const bool fits = wtotal <= CAP;
                     uint32_t *stage = stage_all[wvl];
                     float *sres = sres_all[wvl];
                     unsigned pm0 = 0u, pm1 = 0u;     // per row slot, 1 + the staging position of this lane's key
@@ -468,7 +464,7 @@ select_resident(ResArgs a)
                         const bool need = (needmask >> r) & 1u;
                         const unsigned long long bal = __ballot(need);
                         const int cnt = __popcll(bal);
-                        if (cnt <= SK && fits) {
+                        if (cnt <= CAP - base) {
                             stmask |= 1u << r;
                             // (b) A few keys of the slot may move (the usual case: about 1 % of all keys per
                             // step): their owners copy the packed rows to the wave's staging strip.
@@ -528,7 +524,7 @@ select_resident(ResArgs a)
                     // then the partial sums of a key meet by DPP inside their lane group.  No barrier and no
                     // atomic: since key blocks are dealt round-robin the waves of a head stage about the same
                     // number of keys.
-                    const int total = fits ? wtotal : 0;
+                    const int total = base;
                     if (total > 0) {
                         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                         __builtin_amdgcn_wave_barrier();
