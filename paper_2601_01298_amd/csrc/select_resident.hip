@@ -374,6 +374,7 @@ select_resident(ResArgs a)
                     unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
                     unsigned rowmask = 0u;           // bit r: some key of row slot r may move (wave-uniform)
                     float ns = 0.0f;                 // squared norm of the landmark (set once its pair has arrived)
+                    uint32_t lmo = 0u;
                     constexpr bool MIX = RLDS > 0;   // groups of 3 + 1
                     constexpr int NG = MIX ? RLDS : (R + 3) / 4;
                     static_assert(!MIX || (RREG == 3 * RLDS), "a group is three register rows and one LDS row");
@@ -435,6 +436,7 @@ select_resident(ResArgs a)
                                 nsp = __builtin_amdgcn_fdot2_f32_bf16(lw, lw, 0.0f, false);
                             }
                             ns = wave_fsum(nsp);
+                            lmo = (uint32_t)__shfl_xor((int)lmw, LPK);   // for the staged evaluation: the other packed word
                         }
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) {
@@ -535,7 +537,7 @@ select_resident(ResArgs a)
                         // a lane takes packed words `part` and `part + LPK` of its key; of the landmark row it holds
                         // one of the two already (lmw), the lane LPK further on holds the other
                         const int sub = ln / LPK, part = ln % LPK;
-                        const uint32_t other = (uint32_t)__shfl_xor((int)lmw, LPK);
+                        const uint32_t other = lmo;
                         const bool odd = (sub & 1) != 0;
                         const uint32_t wa = odd ? other : lmw, wb = odd ? lmw : other;
                         const float l0 = __uint_as_float(wa << 16), l1 = __uint_as_float(wa & 0xFFFF0000u);
