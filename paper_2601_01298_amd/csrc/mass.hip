@@ -107,8 +107,7 @@ mass_logits(const void *__restrict__ Kv, const void *__restrict__ Qv, float *__r
                     float acc = 0.0f;
 #pragma unroll
                     for (int e = 0; e < PER; ++e) acc = fmaf(f[e], qf[j][e], acc);
-#pragma unroll
-                    for (int o = 1; o < LPR; o <<= 1) acc += __shfl_xor(acc, o);
+                    acc = lane_group_sum<LPR>(acc);
                     const float zz = acc * scale2;
                     if (i < hi) {
                         if (sub == 0) z[(size_t)(kvh * g + j) * L + i] = zz;

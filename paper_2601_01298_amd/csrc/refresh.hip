@@ -92,8 +92,7 @@ append_sweep(const void *__restrict__ Kv, const float *__restrict__ rho_old, flo
                     const float t = x[u][e] - y[e];
                     acc = fmaf(t, t, acc);
                 }
-#pragma unroll
-                for (int o = 1; o < LPR; o <<= 1) acc += __shfl_xor(acc, o);
+                acc = lane_group_sum<LPR>(acc);
                 const float w = (r0 + u * RP + rsub < hi) ? __builtin_amdgcn_exp2f(-acc * s2) : 0.0f;
                 add[u] += w;
                 col += w;

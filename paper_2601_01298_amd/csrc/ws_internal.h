@@ -10,6 +10,28 @@ constexpr int kWave = 64;
 
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
+// Sum over aligned groups of LPR consecutive lanes (LPR a power of two); every lane of a group ends up with
+// the group's sum.  Inside a row of 16 lanes the partners are reached by DPP operands of the add itself
+// (swap in pairs, swap pairs in quads, mirror 8, mirror 16: the same partners as xor 1, 2, 4, 8, so the
+// result is the xor butterfly's bit for bit); only wider groups go through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add_f32(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+template <int LPR>
+__device__ __forceinline__ float lane_group_sum(float v)
+{
+    if (LPR >= 2) v = dpp_add_f32<0xB1>(v);      // quad_perm [1,0,3,2]
+    if (LPR >= 4) v = dpp_add_f32<0x4E>(v);      // quad_perm [2,3,0,1]
+    if (LPR >= 8) v = dpp_add_f32<0x141>(v);     // row_half_mirror
+    if (LPR >= 16) v = dpp_add_f32<0x140>(v);    // row_mirror
+    if (LPR >= 32) v += __shfl_xor(v, 16);
+    if (LPR >= 64) v += __shfl_xor(v, 32);
+    return v;
+}
+
 // ---- density -------------------------------------------------------------------------
 // Keys per head are padded to a multiple of 512 in the per-key side records.
 static inline int density_lpad(int L) { return (int)round_up((size_t)L, 512); }
