@@ -15,6 +15,8 @@ namespace ws {
 
 namespace {
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
 constexpr int kAppTile = 2048;
 constexpr int kAppMaxM = 32;
 
@@ -72,7 +74,9 @@ append_sweep(const void *__restrict__ Kv, const float *__restrict__ rho_old, flo
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int i = min(r0 + u * RP + rsub, hi - 1);
-            q[u] = *reinterpret_cast<const uint4 *>(Kh + ((size_t)i * D + sub * PER) * ES);
+            // the keys stream through once: loads marked non-temporal keep them from displacing anything cached
+            const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(Kh + ((size_t)i * D + sub * PER) * ES));
+            q[u] = make_uint4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
