@@ -13,9 +13,9 @@
 // Only about 1 % of the keys get closer to the chosen set in a step.  A dot-product screen on the
 // packed bf16 pairs (|k-s|^2 = |k|^2 + |s|^2 - 2 k.s, v_dot2c_f32_bf16) with a proven error margin
 // finds the keys that cannot move; the rest are evaluated exactly, by direct differences in fp32:
-// their owners copy the rows to a staging strip of the wave, which then evaluates them one by one
-// (d = 64: two at a time), a lane per packed pair.  The screen only skips work, it never decides a
-// value.
+// their owners copy the rows to a staging strip of the wave, which then evaluates them a few per
+// pass (d = 64: four, 16 lanes sharing a key), each lane two packed pairs.  The screen only skips
+// work, it never decides a value.
 //
 // A head is shared by up to 32 workgroups of 4 waves, placed on one accelerator die.  A step needs
 // two maxima over all keys of the head, the second depending on the first: D_max, then the best
@@ -338,7 +338,7 @@ select_resident(ResArgs a)
                     typedef const uint32_t __attribute__((address_space(4))) *cptr_t;
                     const cptr_t lp = (cptr_t)(uintptr_t)(Kh + (size_t)prev * D);
                     // its squared norm: one packed pair per lane, summed over the wave
-                    // (lane l also keeps pair l mod D/2 of the landmark for the one-by-one evaluation below)
+                    // (lane l also keeps pair l mod D/2 of the landmark for the staged evaluation below)
                     const uint32_t lmw = reinterpret_cast<const uint32_t *>(Kh + (size_t)prev * D)[lane % DW];
                     const int wvl = tid >> 6;
                     // Exact evaluation widens the packed bf16 pairs on the fly.  Shift count and mask go
