@@ -418,7 +418,8 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
             __syncthreads();
             const int J = (I + j) % nB;
             float *dst = colpart + ((size_t)hl * nBoth + (j - 1)) * Lpad + (size_t)J * BM;
-            for (int c = tid; c < BM; c += 256) dst[c] = ((cs[0][c] + cs[1][c]) + cs[2][c]) + cs[3][c];
+            // written once, read once by the last kernel: non-temporal, so the partial sums do not push the key tiles out of the L2
+            for (int c = tid; c < BM; c += 256) __builtin_nontemporal_store(((cs[0][c] + cs[1][c]) + cs[2][c]) + cs[3][c], dst + c);
         }
         __syncthreads();
     }
@@ -449,7 +450,16 @@ density_finish(const float *__restrict__ rowsum, const float *__restrict__ colpa
     if (i >= L) return;
     float t = rowsum[(size_t)hl * Lpad + i];
     const float *cp = colpart + (size_t)hl * nBoth * Lpad + i;
-    for (int sl = 0; sl < nBoth; ++sl) t += cp[(size_t)sl * Lpad];
+    // slot order is fixed; eight loads are in flight at a time
+    int sl = 0;
+    for (; sl + 8 <= nBoth; sl += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(cp + (size_t)(sl + j) * Lpad);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t += v[j];
+    }
+    for (; sl < nBoth; ++sl) t += __builtin_nontemporal_load(cp + (size_t)sl * Lpad);
     rho[(size_t)(head0 + hl) * L + i] = t / (float)L;
 }
 
