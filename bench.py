@@ -159,6 +159,14 @@ def main() -> int:
         "attend": {"bound": "hbm", "achieved": bytes_attend / (stage_ms["attend"] * 1e-3) / 1e9,
                    "peak": PEAK_HBM_GBS, "unit": "GB/s"},
     }
+    sym = bf16 and w.L >= 4 * (512 if w.d == 64 else 256)      # the symmetric sweep serves this shape
+    if sym:
+        # What the sweep is bound by in practice is the vector pipe, not the matrix core: every unordered pair
+        # costs multiply + v_exp_f32 + two adds = 4 + 16 + 4 + 4 cycles per 64 pairs on one of 1024 SIMDs.
+        pairs = 0.5 * w.L * w.L * w.H
+        floor_ms = pairs / 64.0 * 28.0 / 1024.0 / 2.4e9 * 1e3
+        per_stage["density"]["alu"] = {"bound": "alu", "cycles_per_64_pairs": 28, "clock_ghz": 2.4,
+                                       "floor_ms": floor_ms, "frac": floor_ms / stage_ms["density"]}
     traffic = {}
     if os.path.exists(args.traffic_json):
         try:
@@ -171,7 +179,7 @@ def main() -> int:
         per_stage[s]["ms"] = stage_ms[s]
     dominant = max(stages, key=lambda s: stage_ms[s])
     roofline = dict(per_stage[dominant])
-    kernel_of = {"density": "density_sym" if (bf16 and w.L >= 4 * (512 if w.d == 64 else 256)) else "density_sweep",
+    kernel_of = {"density": "density_sym" if sym else "density_sweep",
                  "select": "select_resident" if ws.ws_synapse_select_is_resident(dt, w.H, w.L, w.d) else "select_stream",
                  "gather": "gather_rows", "attend": "attend_bf16" if bf16 else "attend_f32"}
     roofline["kernel"] = kernel_of[dominant]
