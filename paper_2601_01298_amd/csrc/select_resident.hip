@@ -326,140 +326,131 @@ select_resident(ResArgs a)
         }
 
         {
-            // Fetch of a landmark's row and the screen of every resident key against it, as one piece of code that
-            // takes the landmark's index: it runs for the landmark just chosen and, ahead of time, for the one that is
-            // expected next (see the exchange).
-            auto fetch_screen = [&](int lm_idx, uint32_t (&lws)[DW], uint32_t &lmw, uint32_t &lmo, unsigned &needmask,
-                                    unsigned &rowmask, float &ns) {
-                needmask = 0u;
-                rowmask = 0u;
-                // The landmark row is the same for every lane: read it through the constant address
-                // space (K is never written while the kernel runs) so it arrives by scalar loads in
-                // SGPRs and serves as a broadcast operand instead of occupying VGPRs.
-                typedef const uint32_t __attribute__((address_space(4))) *cptr_t;
-                const cptr_t lp = (cptr_t)(uintptr_t)(Kh + (size_t)lm_idx * D);
-                // its squared norm: one packed pair per lane, summed over the wave
-                // (lane l also keeps pair l mod D/2 of the landmark for the staged evaluation below)
-                lmw = reinterpret_cast<const uint32_t *>(Kh + (size_t)lm_idx * D)[lane % DW];
-                // (a) Screen.  Most keys are far from the new landmark and keep their D.  With
-                // n = |k|^2, |k_i - s|^2 = n_i + n_s - 2 k_i.s, and the dot product runs on packed bf16
-                // pairs (v_dot2c_f32_bf16: two elements per instruction, a sixth of the work of
-                // widening, subtracting and squaring).  Its rounding and cancellation error is below
-                // 2^-17 (n_i + n_s); a row slot goes on to an exact evaluation unless, for every lane,
-                // the screened value exceeds D_i^2 by more than 2^-14 (n_i + n_s).  So the screen never
-                // changes a result: it only skips evaluations that cannot lower D.
-                // The packed landmark words are pinned in SGPRs for the whole step (the empty asm keeps
-                // the compiler from re-fetching them in front of every row slot).
-    #pragma unroll
-                for (int i = 0; i < DW; ++i) lws[i] = lp[i];
-                if (R > 4)      // one group of row slots reads them once anyway
-    #pragma unroll
-                for (int i = 0; i < DW; i += 16)
-                    asm volatile(""
-                                 : "+s"(lws[i]), "+s"(lws[i + 1]), "+s"(lws[i + 2]), "+s"(lws[i + 3]), "+s"(lws[i + 4]),
-                                   "+s"(lws[i + 5]), "+s"(lws[i + 6]), "+s"(lws[i + 7]), "+s"(lws[i + 8]),
-                                   "+s"(lws[i + 9]), "+s"(lws[i + 10]), "+s"(lws[i + 11]), "+s"(lws[i + 12]),
-                                   "+s"(lws[i + 13]), "+s"(lws[i + 14]), "+s"(lws[i + 15]));
-                // Row slots are screened four at a time so that four independent dot-product chains
-                // interleave (one chain alone runs at the latency of the instruction, not its rate).
-                // With rows parked in LDS a group is three register rows and one LDS row, whose 16-byte
-                // pieces are read two pieces ahead of their use: the LDS latency hides behind the
-                // dot products of two pieces instead of stalling every piece.
-                constexpr bool MIX = RLDS > 0;   // groups of 3 + 1
-                constexpr int NG = MIX ? RLDS : (R + 3) / 4;
-                static_assert(!MIX || (RREG == 3 * RLDS), "a group is three register rows and one LDS row");
-    #pragma unroll
-                for (int g = 0; g < NG; ++g) {
-                    // row slot behind position rr of this group (-1: none)
-                    auto rowof = [&](int rr) -> int {
-                        if (MIX) return rr < 3 ? 3 * g + rr : RREG + g;
-                        return 4 * g + rr < R ? 4 * g + rr : -1;
-                    };
-                    float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                    uint4 pf[3];                 // LDS row: pieces c, c+1, c+2 in flight
-                    if (MIX) {
-                        pf[0] = lrows[(g * NV + 0) * 256 + tid];
-                        pf[1] = lrows[(g * NV + 1) * 256 + tid];
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-    #pragma unroll
-                    for (int c = 0; c < NV; ++c) {
-                        if (MIX) {
-                            if (c + 2 < NV) pf[(c + 2) % 3] = lrows[(g * NV + c + 2) * 256 + tid];
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        uint32_t w4[4][4];
-    #pragma unroll
-                        for (int rr = 0; rr < 4; ++rr) {
-                            const int r = rowof(rr);
-                            if (r >= 0 && r < RREG) {
-                                w4[rr][0] = kr[r >= 0 && r < RREG ? r : 0][4 * c];
-                                w4[rr][1] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 1];
-                                w4[rr][2] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 2];
-                                w4[rr][3] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 3];
-                            } else if (r >= 0) {
-                                const uint4 q = pf[c % 3];
-                                w4[rr][0] = q.x;
-                                w4[rr][1] = q.y;
-                                w4[rr][2] = q.z;
-                                w4[rr][3] = q.w;
-                            } else {
-                                w4[rr][0] = w4[rr][1] = w4[rr][2] = w4[rr][3] = 0u;
-                            }
-                        }
-    #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-    #pragma unroll
-                            for (int rr = 0; rr < 4; ++rr)
-                                if (rowof(rr) >= 0)
-                                    dot[rr] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w4[rr][j]),
-                                                                              __builtin_bit_cast(bf16x2_t, lws[4 * c + j]),
-                                                                              dot[rr], false);
-                        if (MIX) __builtin_amdgcn_sched_barrier(0);
-                    }
-                    if (g == 0) {
-                        // the landmark's own squared norm: one packed pair per lane, summed over the wave
-                        // (used only now, so the vector load above overlaps the first dot-product chains)
-                        float nsp = 0.0f;
-                        if (lane < DW) {
-                            const bf16x2_t lw = __builtin_bit_cast(bf16x2_t, lmw);
-                            nsp = __builtin_amdgcn_fdot2_f32_bf16(lw, lw, 0.0f, false);
-                        }
-                        ns = wave_fsum(nsp);
-                        lmo = (uint32_t)__shfl_xor((int)lmw, LPK);   // for the staged evaluation: the other packed word
-                    }
-    #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const int r = rowof(rr);
-                        if (r >= 0) {
-                            const float nsum = nrm[r * 256 + tid] + ns;
-                            const float d2a = fmaf(-2.0f, dot[rr], nsum);
-                            const bool need = fmaf(nsum, -6.103515625e-5f, d2a) < Dv[r] * Dv[r];
-                            const int cnt = __popcll(__ballot(need));
-                            if (need) needmask |= 1u << r;
-                            if (cnt > 0) rowmask |= 1u << r;
-                        }
-                    }
-                }
-            };
-
             int prev = 0;
             unsigned dprev = 0xFFFFFFFFu;    // bits of the D_max the last step ended with (none yet)
             for (t = 0; t < a.k; ++t) {
                 unsigned lbits = 0u;
                 if (t > 0) {
-                    // ---- distance of every resident key to landmark `prev`: fetch of its row, then the screen.
-                    // Both sit in one piece of code that takes the landmark's index, so that it can also run ahead
-                    // of time for a landmark that is only expected (see the exchange below).
+                    // ---- distance of every resident key to landmark `prev`
+                    // The landmark row is the same for every lane: read it through the constant address
+                    // space (K is never written while the kernel runs) so it arrives by scalar loads in
+                    // SGPRs and serves as a broadcast operand instead of occupying VGPRs.
+                    typedef const uint32_t __attribute__((address_space(4))) *cptr_t;
+                    const cptr_t lp = (cptr_t)(uintptr_t)(Kh + (size_t)prev * D);
+                    // its squared norm: one packed pair per lane, summed over the wave
+                    // (lane l also keeps pair l mod D/2 of the landmark for the staged evaluation below)
+                    const uint32_t lmw = reinterpret_cast<const uint32_t *>(Kh + (size_t)prev * D)[lane % DW];
                     const int wvl = tid >> 6;
+                    // Exact evaluation widens the packed bf16 pairs on the fly.  Shift count and mask go
+                    // through an empty asm so the compiler cannot treat the widened values as loop-invariant
+                    // and keep a second, twice as large copy of the keys.
+                    unsigned sh16 = 16u, mhi16 = 0xFFFF0000u;
+                    asm volatile("" : "+s"(sh16), "+s"(mhi16));
+                    // (a) Screen.  Most keys are far from the new landmark and keep their D.  With
+                    // n = |k|^2, |k_i - s|^2 = n_i + n_s - 2 k_i.s, and the dot product runs on packed bf16
+                    // pairs (v_dot2c_f32_bf16: two elements per instruction, a sixth of the work of
+                    // widening, subtracting and squaring).  Its rounding and cancellation error is below
+                    // 2^-17 (n_i + n_s); a row slot goes on to an exact evaluation unless, for every lane,
+                    // the screened value exceeds D_i^2 by more than 2^-14 (n_i + n_s).  So the screen never
+                    // changes a result: it only skips evaluations that cannot lower D.
+                    // The packed landmark words are pinned in SGPRs for the whole step (the empty asm keeps
+                    // the compiler from re-fetching them in front of every row slot).
+                    uint32_t lws[DW];
+#pragma unroll
+                    for (int i = 0; i < DW; ++i) lws[i] = lp[i];
+                    if (R > 4)      // one group of row slots reads them once anyway
+#pragma unroll
+                    for (int i = 0; i < DW; i += 16)
+                        asm volatile(""
+                                     : "+s"(lws[i]), "+s"(lws[i + 1]), "+s"(lws[i + 2]), "+s"(lws[i + 3]), "+s"(lws[i + 4]),
+                                       "+s"(lws[i + 5]), "+s"(lws[i + 6]), "+s"(lws[i + 7]), "+s"(lws[i + 8]),
+                                       "+s"(lws[i + 9]), "+s"(lws[i + 10]), "+s"(lws[i + 11]), "+s"(lws[i + 12]),
+                                       "+s"(lws[i + 13]), "+s"(lws[i + 14]), "+s"(lws[i + 15]));
+                    // Row slots are screened four at a time so that four independent dot-product chains
+                    // interleave (one chain alone runs at the latency of the instruction, not its rate).
+                    // With rows parked in LDS a group is three register rows and one LDS row, whose 16-byte
+                    // pieces are read two pieces ahead of their use: the LDS latency hides behind the
+                    // dot products of two pieces instead of stalling every piece.
                     unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
                     unsigned rowmask = 0u;           // bit r: some key of row slot r may move (wave-uniform)
                     float ns = 0.0f;                 // squared norm of the landmark (set once its pair has arrived)
-                    uint32_t lmo = 0u, lmw = 0u;
-                    uint32_t lws[DW];
-                    unsigned sh16 = 16u, mhi16 = 0xFFFF0000u;
-                    asm volatile("" : "+s"(sh16), "+s"(mhi16));
-                    fetch_screen(prev, lws, lmw, lmo, needmask, rowmask, ns);
+                    uint32_t lmo = 0u;
+                    constexpr bool MIX = RLDS > 0;   // groups of 3 + 1
+                    constexpr int NG = MIX ? RLDS : (R + 3) / 4;
+                    static_assert(!MIX || (RREG == 3 * RLDS), "a group is three register rows and one LDS row");
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) {
+                        // row slot behind position rr of this group (-1: none)
+                        auto rowof = [&](int rr) -> int {
+                            if (MIX) return rr < 3 ? 3 * g + rr : RREG + g;
+                            return 4 * g + rr < R ? 4 * g + rr : -1;
+                        };
+                        float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        uint4 pf[3];                 // LDS row: pieces c, c+1, c+2 in flight
+                        if (MIX) {
+                            pf[0] = lrows[(g * NV + 0) * 256 + tid];
+                            pf[1] = lrows[(g * NV + 1) * 256 + tid];
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+#pragma unroll
+                        for (int c = 0; c < NV; ++c) {
+                            if (MIX) {
+                                if (c + 2 < NV) pf[(c + 2) % 3] = lrows[(g * NV + c + 2) * 256 + tid];
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            uint32_t w4[4][4];
+#pragma unroll
+                            for (int rr = 0; rr < 4; ++rr) {
+                                const int r = rowof(rr);
+                                if (r >= 0 && r < RREG) {
+                                    w4[rr][0] = kr[r >= 0 && r < RREG ? r : 0][4 * c];
+                                    w4[rr][1] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 1];
+                                    w4[rr][2] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 2];
+                                    w4[rr][3] = kr[r >= 0 && r < RREG ? r : 0][4 * c + 3];
+                                } else if (r >= 0) {
+                                    const uint4 q = pf[c % 3];
+                                    w4[rr][0] = q.x;
+                                    w4[rr][1] = q.y;
+                                    w4[rr][2] = q.z;
+                                    w4[rr][3] = q.w;
+                                } else {
+                                    w4[rr][0] = w4[rr][1] = w4[rr][2] = w4[rr][3] = 0u;
+                                }
+                            }
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                for (int rr = 0; rr < 4; ++rr)
+                                    if (rowof(rr) >= 0)
+                                        dot[rr] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w4[rr][j]),
+                                                                                  __builtin_bit_cast(bf16x2_t, lws[4 * c + j]),
+                                                                                  dot[rr], false);
+                            if (MIX) __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if (g == 0) {
+                            // the landmark's own squared norm: one packed pair per lane, summed over the wave
+                            // (used only now, so the vector load above overlaps the first dot-product chains)
+                            float nsp = 0.0f;
+                            if (lane < DW) {
+                                const bf16x2_t lw = __builtin_bit_cast(bf16x2_t, lmw);
+                                nsp = __builtin_amdgcn_fdot2_f32_bf16(lw, lw, 0.0f, false);
+                            }
+                            ns = wave_fsum(nsp);
+                            lmo = (uint32_t)__shfl_xor((int)lmw, LPK);   // for the staged evaluation: the other packed word
+                        }
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) {
+                            const int r = rowof(rr);
+                            if (r >= 0) {
+                                const float nsum = nrm[r * 256 + tid] + ns;
+                                const float d2a = fmaf(-2.0f, dot[rr], nsum);
+                                const bool need = fmaf(nsum, -6.103515625e-5f, d2a) < Dv[r] * Dv[r];
+                                const int cnt = __popcll(__ballot(need));
+                                if (need) needmask |= 1u << r;
+                                if (cnt > 0) rowmask |= 1u << r;
+                            }
+                        }
+                    }
                     // row slots whose keys no longer fit the wave's staging strip (the first steps, when most keys
                     // move) are evaluated whole instead
                     int base = 0;
