@@ -150,3 +150,16 @@ def test_selection_kernel_choice_is_host_logic(lib, monkeypatch):
     c = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 4096, 32768, 64)
     assert a >= 384 * 32768 * 16 and c - a < (4096 - 384) * 32768 * 16 + (2 << 30)
     assert c < 4096 * 32768 * 16 + (5 << 30)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: asking for more ends with a message and a non-zero status, before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
