@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libws_synapse.so")
-SOURCES = ["api.hip", "density.hip", "select.hip", "select_resident.hip", "gather.hip", "attend.hip",
+SOURCES = ["api.hip", "density.hip", "select.hip", "select_resident.hip", "select_resident_ahead.hip", "gather.hip", "attend.hip",
            "mass.hip", "refresh.hip", "gate.hip", "inject.hip"]
 # packed fp32 VALU forms are switched off on purpose (some of them have misbehaved on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -725,7 +725,8 @@ hipError_t launch_select_resident(const void *K, int H, int L, int d, const floa
         if (s.rreg == 1) return run<64, 1, 0>(a, st);
         if (s.rreg == 2) return run<64, 2, 0>(a, st);
         if (s.rreg == 4) return run<64, 4, 0>(a, st);
-        return run<64, 6, 2>(a, st);
+        // eight rows per lane: the variant that screens the expected next landmark during the exchange
+        return launch_select_resident_ahead(K, H, L, rho, k, alpha, idx, score_out, a.slots, a.fail, a.groups, a.wgpg, st);
     }
     if (s.rreg == 1) return run<128, 1, 0>(a, st);
     if (s.rreg == 2) return run<128, 2, 0>(a, st);

@@ -58,6 +58,11 @@ bool resident_select_supported(int H, int L, int d, bool bf16);
 size_t resident_select_workspace_bytes(int H, int L, int d);
 hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
                                   int32_t *idx, float *score_out, void *ws, hipStream_t st);
+// the same kernel with the next step's screen run during the exchange; d = 64 and eight rows per lane only,
+// called by launch_select_resident with the workspace laid out and cleared
+hipError_t launch_select_resident_ahead(const void *K, int H, int L, const float *rho, int k, float alpha, int32_t *idx,
+                                        float *score_out, unsigned long long *slots, int *fail, int groups, int wgpg,
+                                        hipStream_t st);
 
 // ---- gather --------------------------------------------------------------------------
 hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int L,
