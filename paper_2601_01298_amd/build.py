@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libws_synapse.so")
 SOURCES = ["api.hip", "density.hip", "select.hip", "select_resident.hip", "select_resident_ahead.hip", "gather.hip", "attend.hip",
            "mass.hip", "refresh.hip", "gate.hip", "inject.hip"]
 # packed fp32 VALU forms are switched off on purpose (some of them have misbehaved on the test machines)
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

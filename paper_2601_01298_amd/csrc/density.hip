@@ -255,6 +255,30 @@ density_sweep(const typename TR::Elem *__restrict__ K, const uint4 *__restrict__
     }
 }
 
+
+// LDS-only barrier: waits for this wave's LDS traffic, not for its global loads
+__device__ __forceinline__ void lds_only_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): lane i of the wave lands at
+// lds_base + 16 * i.  Completion is counted by vmcnt like any vector load; the compiler does not see it, so the
+// caller waits explicitly before the barrier that publishes the data.
+__device__ __forceinline__ void dma16(const void *g, const void *lds_base)
+{
+    const unsigned la =
+        __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const void *)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // ------------------------------------------------------------------------------------------
 // Symmetric sweep (bf16 keys, heads of at least a few row blocks).
 //
@@ -269,9 +293,11 @@ density_sweep(const typename TR::Elem *__restrict__ K, const uint4 *__restrict__
 // order, so the result does not depend on scheduling.
 //
 // The 4 waves of a workgroup own different rows (RTW tiles of 32 each) and share the stream of
-// column tiles: 64 key rows per stage are copied global -> LDS with coalesced 16-byte loads,
-// double-buffered one stage ahead, and read back in MFMA operand layout (16-byte pieces,
-// XOR-swizzled by row so the 8 lanes served per LDS cycle hit 8 different bank groups).
+// column tiles: 64 key rows per stage reach the LDS by asynchronous global -> LDS copies (no
+// registers in between) issued two stages ahead into three rotating buffers, and are read back in
+// MFMA operand layout (16-byte pieces, XOR-swizzled by row so the 8 lanes served per LDS cycle hit
+// 8 different bank groups; the swizzle is applied on the global side of the copy).  One LDS-only
+// barrier per stage publishes the stage and retires the buffer two stages back.
 // ------------------------------------------------------------------------------------------
 template <int D, int RTW, bool BOTH, bool DIAG>
 __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], const bf16x8_t (&b)[D / 16 + 1],
@@ -289,30 +315,32 @@ __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], c
 #pragma unroll
     for (int rt = 0; rt < RTW; ++rt) {
         f32x16_t &cur = acc[rt & 1], &nxt = acc[(rt + 1) & 1];
-        if (rt + 1 < RTW) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) nxt[r] = 0.0f;
-#pragma unroll
-            for (int kk = 0; kk < NS; ++kk)
-                nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt + 1][kk], b[kk], nxt, 0, 0, 0);
-        }
         if (DIAG && rt == diag_rt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (8 * (r >> 2) + 4 * hb + (r & 3) == n) cur[r] = 0.0f;   // a key's distance to itself
         }
+        if (rt + 1 < RTW) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float w = __builtin_amdgcn_exp2f(cur[r] * s);
-            racc[rt][r] += w;
-            if (BOTH) csum += w;
-        }
-        if (!DIAG && rt + 1 < RTW) {
-            constexpr int VPER = (BOTH ? 64 : 48) / NS;      // vector instructions between two MFMAs
+            for (int r = 0; r < 16; ++r) nxt[r] = 0.0f;
 #pragma unroll
             for (int kk = 0; kk < NS; ++kk) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);
+                nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt + 1][kk], b[kk], nxt, 0, 0, 0);
+#pragma unroll
+                for (int r = (kk * 16 + NS - 1) / NS; r < ((kk + 1) * 16 + NS - 1) / NS; ++r) {
+                    const float w = __builtin_amdgcn_exp2f(cur[r] * s);
+                    racc[rt][r] += w;
+                    if (BOTH) csum += w;
+                }
+                // keeps each MFMA between its shares of the vector work
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float w = __builtin_amdgcn_exp2f(cur[r] * s);
+                racc[rt][r] += w;
+                if (BOTH) csum += w;
             }
         }
     }
@@ -330,8 +358,9 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
     constexpr int SC = 64;                 // key rows per LDS stage
     constexpr int SPB = BM / SC;           // stages per block
     constexpr int NLD = SC * CH / 256;     // 16-byte pieces each thread moves per stage
-    __shared__ uint4 sB[2][SC * CH];
-    __shared__ uint4 sE[2][SC];
+    constexpr int NBUF = 3, PF = NBUF - 1;  // LDS buffers in rotation; stages the copies run ahead
+    __shared__ uint4 sB[NBUF][SC * CH];
+    __shared__ uint4 sE[NBUF][SC];
     __shared__ float cs[4][BM];
 
     const int logical = xcd_contiguous(blockIdx.x, total);
@@ -340,7 +369,7 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
     const uint16_t *Kh = K + (size_t)h * L * D;
     const uint4 *exth = ext + (size_t)h * Lpad;
     const float s = scale[h];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hb = lane >> 5;
 
     bf16x8_t a[RTW][NS];
@@ -361,35 +390,36 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
     const int nblk = 1 + nBoth + ((nB > 1 && (nB & 1) == 0) ? 1 : 0);
     const int nst = nblk * SPB;
 
-    uint4 g[NLD];
-    uint4 ge = make_uint4(0, 0, 0, 0);
-    auto fetch = [&](int sidx) {       // global -> registers, coalesced
+    // Key rows reach the LDS by asynchronous copies issued two stages ahead, already in the swizzled order the
+    // MFMA operand reads expect (slot c of row r holds piece c ^ (r & 7)); three buffers rotate.
+    auto issue = [&](int sidx) {
         const int J = (I + sidx / SPB) % nB;
         const int col0 = J * BM + (sidx % SPB) * SC;
+        const int bi = sidx % NBUF;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int q = tid + 256 * i;
             const int r = q / CH, c = q % CH;
-            g[i] = *reinterpret_cast<const uint4 *>(Kh + (size_t)min(col0 + r, L - 1) * D + c * 8);
+            dma16(Kh + (size_t)min(col0 + r, L - 1) * D + (c ^ (r & 7)) * 8, &sB[bi][wave * 64 + 256 * i]);
         }
-        if (tid < SC) ge = exth[col0 + tid];
-    };
-    auto stash = [&](int buf) {        // registers -> LDS, swizzled
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int q = tid + 256 * i;
-            const int r = q / CH, c = q % CH;
-            sB[buf][r * CH + (c ^ (r & 7))] = g[i];
-        }
-        if (tid < SC) sE[buf][tid] = ge;
+        if (wave == 0) dma16(exth + col0 + lane, &sE[bi][0]);
     };
 
-    fetch(0);
-    stash(0);
-    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (p < nst) issue(p);
     for (int sidx = 0; sidx < nst; ++sidx) {
-        const int buf = sidx & 1;
-        if (sidx + 1 < nst) fetch(sidx + 1);
+        const int buf = sidx % NBUF;
+        // this wave's copies of the stage have landed (those of the next stage may still be in flight) ...
+        if (sidx + 1 < nst) {
+            if (wave == 0) wait_vmcnt<NLD + 1>();
+            else wait_vmcnt<NLD>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        // ... and so have everybody's; all waves are through with the stage before
+        lds_only_barrier();
+        if (sidx + PF < nst) issue(sidx + PF);
         const int j = sidx / SPB, sin = sidx - j * SPB;
         const bool both = j >= 1 && j <= nBoth;
 #pragma unroll 1
@@ -407,13 +437,13 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
                 sym_tile<D, RTW, false, true>(a, b, racc, csum, s, n, hb, ctile - wave * RTW);
             } else if (both) {
                 sym_tile<D, RTW, true, false>(a, b, racc, csum, s, n, hb, -1);
-                csum += __shfl_xor(csum, 32);
-                if (hb == 0) cs[wave][sin * SC + r] = csum;
+                // both half-waves end up with the same sum and store it to the same word: no branch, so the
+                // compiler keeps the additions next to their exponentials
+                cs[wave][sin * SC + r] = csum + __shfl_xor(csum, 32);
             } else {
                 sym_tile<D, RTW, false, false>(a, b, racc, csum, s, n, hb, -1);
             }
         }
-        if (sidx + 1 < nst) stash(buf ^ 1);
         if (both && sin == SPB - 1) {
             __syncthreads();
             const int J = (I + j) % nB;
@@ -421,7 +451,6 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
             // written once, read once by the last kernel: non-temporal, so the partial sums do not push the key tiles out of the L2
             for (int c = tid; c < BM; c += 256) __builtin_nontemporal_store(((cs[0][c] + cs[1][c]) + cs[2][c]) + cs[3][c], dst + c);
         }
-        __syncthreads();
     }
 
     // each wave owns its rows: reduce over the 32 columns held by the lanes of a half-wave
