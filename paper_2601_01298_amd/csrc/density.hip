@@ -264,14 +264,14 @@ __device__ __forceinline__ void lds_only_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): lane i of the wave lands at
-// lds_base + 16 * i.  Completion is counted by vmcnt like any vector load; the compiler does not see it, so the
+// Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): lane i of the wave reads base +
+// byte_offset and lands at lds_base + 16 * i.  Completion is counted by vmcnt like any vector load; the compiler does not see it, so the
 // caller waits explicitly before the barrier that publishes the data.
-__device__ __forceinline__ void dma16(const void *g, const void *lds_base)
+__device__ __forceinline__ void dma16(const void *base /* wave-uniform */, unsigned byte_offset, const void *lds_base)
 {
     const unsigned la =
         __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const void *)lds_base);
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_offset), "s"(base), "s"(la) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -361,7 +361,7 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
     constexpr int NBUF = 3, PF = NBUF - 1;  // LDS buffers in rotation; stages the copies run ahead
     __shared__ uint4 sB[NBUF][SC * CH];
     __shared__ uint4 sE[NBUF][SC];
-    __shared__ float cs[4][BM];
+    __shared__ float cs[4][2][BM];          // column sums of a block: per wave and half-wave
 
     const int logical = xcd_contiguous(blockIdx.x, total);
     const int hl = logical / nB, I = logical - hl * nB;
@@ -379,7 +379,11 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
         const uint16_t *rp = Kh + (size_t)min(row, L - 1) * D;
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) a[rt][kk] = Bf16Tr::load(rp, kk, hb);
-        a[rt][NK] = Bf16Tr::ext_a(exth[row], hb, 0);
+        // the record is {m1..m4, 1,1,1,1} with m1+..+m4 = -n/2: the column side uses it as it is, the row side
+        // swaps its halves, so the extra k-step adds -n_i/2 - n_j/2.  Only the first 8 k-slots are used: the row
+        // side holds zeros in the others, so what the column side holds there does not matter.
+        const uint4 rec = exth[row];
+        a[rt][NK] = __builtin_bit_cast(bf16x8_t, hb ? make_uint4(0, 0, 0, 0) : make_uint4(rec.z, rec.w, rec.x, rec.y));
     }
     float racc[RTW][16];
 #pragma unroll
@@ -392,18 +396,35 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
 
     // Key rows reach the LDS by asynchronous copies issued two stages ahead, already in the swizzled order the
     // MFMA operand reads expect (slot c of row r holds piece c ^ (r & 7)); three buffers rotate.
+    // per-thread constants of the copy: which row of a stage and which (swizzled) 16-byte piece of it
+    int crow[NLD];
+    unsigned cpiece[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int q = tid + 256 * i;
+        crow[i] = q / CH;
+        cpiece[i] = (unsigned)(((q % CH) ^ (crow[i] & 7)) * 16);
+    }
     auto issue = [&](int sidx) {
         const int J = (I + sidx / SPB) % nB;
         const int col0 = J * BM + (sidx % SPB) * SC;
         const int bi = sidx % NBUF;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int q = tid + 256 * i;
-            const int r = q / CH, c = q % CH;
-            dma16(Kh + (size_t)min(col0 + r, L - 1) * D + (c ^ (r & 7)) * 8, &sB[bi][wave * 64 + 256 * i]);
-        }
-        if (wave == 0) dma16(exth + col0 + lane, &sE[bi][0]);
+        for (int i = 0; i < NLD; ++i)
+            dma16(Kh, (unsigned)min(col0 + crow[i], L - 1) * (unsigned)(D * 2) + cpiece[i], &sB[bi][wave * 64 + 256 * i]);
+        if (wave == 0) dma16(exth, (unsigned)(col0 + lane) * 16u, &sE[bi][0]);
     };
+
+    // LDS read positions of this lane: row n of a tile, the swizzled pieces of the NK k-steps
+    const int boff0 = n * CH;
+    int bpiece[NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) bpiece[kk] = (2 * kk + hb) ^ (n & 7);
+    float *csw = &cs[wave][hb][n];
+
+    // The row operands must be in their registers before the first asynchronous copy is issued: the compiler
+    // would otherwise wait for them at their first use inside the loop, with a count that also covers the copies.
+    wait_vmcnt<0>();
 
 #pragma unroll
     for (int p = 0; p < PF; ++p)
@@ -422,14 +443,14 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
         if (sidx + PF < nst) issue(sidx + PF);
         const int j = sidx / SPB, sin = sidx - j * SPB;
         const bool both = j >= 1 && j <= nBoth;
+        const uint4 *sBb = sB[buf] + boff0;          // this lane's row n of the stage, tile 0
+        const uint4 *sEb = sE[buf] + n;
 #pragma unroll 1
         for (int tt = 0; tt < SC / 32; ++tt) {
-            const int r = tt * 32 + n;
             bf16x8_t b[NS];
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk)
-                b[kk] = __builtin_bit_cast(bf16x8_t, sB[buf][r * CH + ((2 * kk + hb) ^ (r & 7))]);
-            b[NK] = Bf16Tr::ext_b(sE[buf][r], hb, 0);
+            for (int kk = 0; kk < NK; ++kk) b[kk] = __builtin_bit_cast(bf16x8_t, sBb[tt * 32 * CH + bpiece[kk]]);
+            b[NK] = __builtin_bit_cast(bf16x8_t, sEb[tt * 32]);
             float csum = 0.0f;
             if (j == 0) {
                 // column tile index inside the block vs this wave's row tiles
@@ -437,9 +458,8 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
                 sym_tile<D, RTW, false, true>(a, b, racc, csum, s, n, hb, ctile - wave * RTW);
             } else if (both) {
                 sym_tile<D, RTW, true, false>(a, b, racc, csum, s, n, hb, -1);
-                // both half-waves end up with the same sum and store it to the same word: no branch, so the
-                // compiler keeps the additions next to their exponentials
-                cs[wave][sin * SC + r] = csum + __shfl_xor(csum, 32);
+                // each half-wave keeps its own partial sum (no cross-lane step, no branch)
+                csw[sin * SC + tt * 32] = csum;
             } else {
                 sym_tile<D, RTW, false, false>(a, b, racc, csum, s, n, hb, -1);
             }
@@ -449,7 +469,10 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
             const int J = (I + j) % nB;
             float *dst = colpart + ((size_t)hl * nBoth + (j - 1)) * Lpad + (size_t)J * BM;
             // written once, read once by the last kernel: non-temporal, so the partial sums do not push the key tiles out of the L2
-            for (int c = tid; c < BM; c += 256) __builtin_nontemporal_store(((cs[0][c] + cs[1][c]) + cs[2][c]) + cs[3][c], dst + c);
+            for (int c = tid; c < BM; c += 256)
+                __builtin_nontemporal_store(((cs[0][0][c] + cs[0][1][c]) + (cs[1][0][c] + cs[1][1][c])) +
+                                                ((cs[2][0][c] + cs[2][1][c]) + (cs[3][0][c] + cs[3][1][c])),
+                                            dst + c);
         }
     }
 
