@@ -162,10 +162,10 @@ def main() -> int:
     sym = bf16 and w.L >= 4 * (512 if w.d == 64 else 256)      # the symmetric sweep serves this shape
     if sym:
         # What the sweep is bound by in practice is the vector pipe, not the matrix core: every unordered pair
-        # costs multiply + v_exp_f32 + two adds = 4 + 16 + 4 + 4 cycles per 64 pairs on one of 1024 SIMDs.
+        # costs multiply + v_exp_f32 + two adds = 4 + 8 + 4 + 4 cycles per 64 pairs on one of 1024 SIMDs.
         pairs = 0.5 * w.L * w.L * w.H
-        floor_ms = pairs / 64.0 * 28.0 / 1024.0 / 2.4e9 * 1e3
-        per_stage["density"]["alu"] = {"bound": "alu", "cycles_per_64_pairs": 28, "clock_ghz": 2.4,
+        floor_ms = pairs / 64.0 * 20.0 / 1024.0 / 2.4e9 * 1e3
+        per_stage["density"]["alu"] = {"bound": "alu", "cycles_per_64_pairs": 20, "clock_ghz": 2.4,
                                        "floor_ms": floor_ms, "frac": floor_ms / stage_ms["density"]}
     traffic = {}
     if os.path.exists(args.traffic_json):
