@@ -396,22 +396,18 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
 
     // Key rows reach the LDS by asynchronous copies issued two stages ahead, already in the swizzled order the
     // MFMA operand reads expect (slot c of row r holds piece c ^ (r & 7)); three buffers rotate.
-    // per-thread constants of the copy: which row of a stage and which (swizzled) 16-byte piece of it
-    int crow[NLD];
-    unsigned cpiece[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int q = tid + 256 * i;
-        crow[i] = q / CH;
-        cpiece[i] = (unsigned)(((q % CH) ^ (crow[i] & 7)) * 16);
-    }
+    // per-thread constants of the copy: which row of a stage and which (swizzled) 16-byte piece of it; the
+    // thread's further pieces of a stage sit 256 / CH rows below with the same swizzle (256 / CH is a multiple of 8)
+    const int crow = tid / CH;
+    const unsigned cpiece = (unsigned)(((tid % CH) ^ (crow & 7)) * 16);
     auto issue = [&](int sidx) {
         const int J = (I + sidx / SPB) % nB;
         const int col0 = J * BM + (sidx % SPB) * SC;
         const int bi = sidx % NBUF;
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
-            dma16(Kh, (unsigned)min(col0 + crow[i], L - 1) * (unsigned)(D * 2) + cpiece[i], &sB[bi][wave * 64 + 256 * i]);
+            dma16(Kh, (unsigned)min(col0 + crow + i * (256 / CH), L - 1) * (unsigned)(D * 2) + cpiece,
+                  &sB[bi][wave * 64 + 256 * i]);
         if (wave == 0) dma16(exth, (unsigned)(col0 + lane) * 16u, &sE[bi][0]);
     };
 

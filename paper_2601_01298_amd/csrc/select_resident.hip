@@ -133,6 +133,9 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
     }
     __syncthreads();
     if (wave == 0) {
+        // The exchange is the critical path of the step: from its first exchange on, the wave that carries it goes
+        // first on its SIMD (a wave's own issue priority).
+        __builtin_amdgcn_s_setprio(3);
         // the 4 waves' entries: every lane reads all of them (same address: a broadcast), no cross-lane step
         unsigned md = max(max(sh.dm[0], sh.dm[1]), max(sh.dm[2], sh.dm[3]));
         unsigned mh = max(max(sh.hi[0], sh.hi[1]), max(sh.hi[2], sh.hi[3]));

@@ -128,9 +128,15 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
     // Between the two barriers most of an exchange is waiting.  That time goes into work for the NEXT step:
     // the screen against the landmark that is expected to win this exchange (the runner-up of the last one).
     const int pred = __builtin_amdgcn_readfirstlane(sh.pred);
-    const bool poster = wave == 0 && nwg > 1;       // the wave that posts and polls for the workgroup
+    // The posting wave alternates with the half of the grid the workgroup is in: two workgroups share a CU,
+    // and this keeps their posting waves off the same SIMD when they are dealt b and b + gridDim/2.
+    const int pw = (blockIdx.x * 2 >= gridDim.x) ? 2 : 0;
+    const bool poster = wave == pw && nwg > 1;       // the wave that posts and polls for the workgroup
     unsigned md = 0u, mh = 0u, ml = 0u, tag = 0u, touched = 0u;
-    if (wave == 0) {
+    if (wave == pw) {
+        // The exchange is the critical path of the step and this wave does more per step than the others: from
+        // its first exchange on it goes first on its SIMD (a wave's own issue priority, nothing to do with streams).
+        __builtin_amdgcn_s_setprio(3);
         // the 4 waves' entries: every lane reads all of them (same address: a broadcast), no cross-lane step
         md = max(max(sh.dm[0], sh.dm[1]), max(sh.dm[2], sh.dm[3]));
         mh = max(max(sh.hi[0], sh.hi[1]), max(sh.hi[2], sh.hi[3]));
@@ -204,7 +210,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
         keep_h = kind == 1 ? gh : 0u;
         keep_l = kind == 1 ? gl : 0u;
     }
-    if (wave == 0 && lane == 0) {
+    if (wave == pw && lane == 0) {
         sh.rdm = md;
         sh.rhi = mh;
         sh.rlo = ml;
@@ -215,7 +221,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
     hi_out = sh.rhi;
     lo_out = sh.rlo;
     const bool fine = sh.abort == 0;
-    if (wave == 0) {
+    if (wave == pw) {
         // The prediction for the next exchange: the best of the other workgroups' candidates.  (The true runner-up
         // may be the winning workgroup's second key; a prediction only has to be right most of the time.)
         int p = -1;
