@@ -398,6 +398,7 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
     // MFMA operand reads expect (slot c of row r holds piece c ^ (r & 7)); three buffers rotate.
     // per-thread constants of the copy: which row of a stage and which (swizzled) 16-byte piece of it; the
     // thread's further pieces of a stage sit 256 / CH rows below with the same swizzle (256 / CH is a multiple of 8)
+    // (byte offsets inside a head are 32-bit: the entry point admits L < 2^24 rows of at most 256 bytes)
     const int crow = tid / CH;
     const unsigned cpiece = (unsigned)(((tid % CH) ^ (crow & 7)) * 16);
     auto issue = [&](int sidx) {
