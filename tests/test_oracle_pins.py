@@ -225,6 +225,139 @@ def test_select_verify_mode(oracle):
     assert oracle.select_verify(K, rho, 25, 0.5, rep)[0] == -2
 
 
+def verify_from_definition(K, u, alpha, cand):
+    """What verify mode must report, from the definition alone: at step t the landmarks are the
+    CANDIDATE's first t entries; the pick is the lowest index among the exact maxima of the score,
+    the deficit (best - score[cand[t]]) / |best| (0 where the candidate is that pick)."""
+    picks, deficits, chosen = [], [], []
+    for t, c in enumerate(cand):
+        if t == 0 and alpha == 1.0:
+            best_i, best, sc_c = 0, alpha, alpha
+        else:
+            sc, free = scores_from_definition(K, u, chosen, alpha)
+            best = max(sc[i] for i in free)
+            best_i = [i for i in free if sc[i] == best][0]
+            sc_c = sc[c]
+        picks.append(best_i)
+        deficits.append(0.0 if best_i == c else (best - sc_c) / abs(best))
+        chosen.append(int(c))
+    return picks, deficits
+
+
+def verify_cases(select, alpha):
+    """A small cloud and candidate chains that leave the greedy chain in different ways: the step's
+    runner-up, a mid-ranked point, another first landmark, the last step, and two forks in one
+    chain.  `select(K, rho, k, alpha)` returns the greedy chain the candidates start from."""
+    L, k = 60, 14
+    K = small_cloud(L, 4, 26)
+    rho = np.exp(logsumexp(-cdist(K, K, "sqeuclidean") / (2 * 0.9 * 0.9), axis=1)) / L
+    u = rho.min() / rho
+    idx = select(K, rho, k, alpha)
+
+    def ranked(chosen):                       # free points, best score first (lowest index on ties)
+        sc, free = scores_from_definition(K, u, chosen, alpha)
+        return sorted(free, key=lambda i: (-sc[i], i))
+
+    cands = []
+    for t_fork, rank in [(3, 1), (7, len(idx)), (0, 1), (0, 5), (k - 1, 1)]:
+        cand = idx.tolist()[:t_fork]
+        order = ranked(cand) if not (t_fork == 0 and alpha == 1.0) else list(range(L))
+        cand.append(order[min(rank, len(order) - 1)])
+        while len(cand) < k:                  # continue greedily along the candidate's own prefix
+            cand.append(ranked(cand)[0])
+        cands.append(cand)
+    cand = cands[0][:9]                       # a second fork, mid-ranked ...
+    cand.append(ranked(cand)[20])
+    while len(cand) < k:
+        cand.append(ranked(cand)[1])          # ... and the runner-up at every later step
+    cands.append(cand)
+    return K, rho, u, k, cands
+
+
+def verify_mismatches(verify, K, rho, u, k, alpha, cands):
+    """Number of candidates on which `verify` (returning forks, picks, deficits) departs from the
+    definition in any pick, any deficit (1e-12) or the fork count."""
+    wrong = 0
+    for cand in cands:
+        want_pick, want_def = verify_from_definition(K, u, alpha, cand)
+        forks, pick, deficit = verify(K, rho, k, alpha, np.array(cand, dtype=np.int32))
+        ok = (list(pick) == want_pick and np.allclose(deficit, want_def, rtol=1e-12, atol=1e-15)
+              and forks == sum(1 for a, b in zip(cand, want_pick) if a != b))
+        wrong += not ok
+    return wrong
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.25, 0.5, 1.0])
+def test_select_verify_values_along_candidate_prefix(oracle, alpha):
+    """Pick and deficit of every step, also after a fork, against the definition."""
+    K, rho, u, k, cands = verify_cases(lambda *a: oracle.select(*a)[0], alpha)
+    assert verify_mismatches(oracle.select_verify, K, rho, u, k, alpha, cands) == 0
+    for n, cand in enumerate(cands):
+        want_pick, want_def = verify_from_definition(K, u, alpha, cand)
+        assert want_pick != cand
+        if not (alpha == 1.0 and n in (2, 3)):     # (a first landmark other than 0 at alpha = 1 costs nothing)
+            assert max(want_def) > 1e-3       # the planted forks are real deficits, not rounding
+
+
+MUTANTS = [   # (text in ws_oracle.c, replacement): slips a verify mode could plausibly contain
+    ("(t1 - sc) / fabs(t1)", "(t1 - t2) / fabs(t1)"),            # deficit against the runner-up
+    ("(t1 - sc) / fabs(t1)", "(t1 - sc) / fabs(sc)"),            # another denominator
+    ("absorb_landmark(K, L, d, c, D, chosen);", "absorb_landmark(K, L, d, s, D, chosen);"),  # oracle's prefix
+    ("if (i == probe) *probe_score = s;", "if (i == probe) *probe_score = c;"),   # coverage term for the score
+]
+
+
+@pytest.mark.parametrize("mutant", range(len(MUTANTS)))
+def test_select_verify_pins_catch_planted_mistakes(oracle, tmp_path, mutant):
+    """The value pins above must fail on a verify mode with a planted slip.  The slip is planted in
+    a private copy of the oracle's source, compiled here on the CPU."""
+    import ctypes
+    import subprocess
+    old, new = MUTANTS[mutant]
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "ws_oracle.c")).read()
+    assert src.count(old) == 1
+    cfile, so = tmp_path / "mutant.c", tmp_path / "libmutant.so"
+    cfile.write_text(src.replace(old, new))
+    subprocess.run(["gcc", "-O1", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", "-o", str(so), str(cfile), "-lm"],
+                   check=True)
+    lib = ctypes.CDLL(str(so))
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+    lib.wso_select_verify.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ip, ip, dp]
+    lib.wso_select_verify.restype = ctypes.c_int
+
+    def verify(K, rho, k, alpha, cand):
+        K = np.ascontiguousarray(K, dtype=np.float64)
+        rho = np.ascontiguousarray(rho, dtype=np.float64)
+        pick, deficit = np.zeros(k, dtype=np.int32), np.zeros(k)
+        forks = lib.wso_select_verify(K.ctypes.data_as(dp), rho.ctypes.data_as(dp), K.shape[0], K.shape[1], k, alpha,
+                                      cand.ctypes.data_as(ip), pick.ctypes.data_as(ip), deficit.ctypes.data_as(dp))
+        return forks, pick.tolist(), deficit
+
+    wrong = 0
+    for alpha in (0.25, 0.5):
+        K, rho, u, k, cands = verify_cases(lambda *a: oracle.select(*a)[0], alpha)
+        wrong += verify_mismatches(verify, K, rho, u, k, alpha, cands)
+    assert wrong > 0, f"mutant {old!r} -> {new!r} passes the verify pins"
+
+
+def test_select_verify_exact_tie_and_zero_radius(oracle):
+    # exact tie (integer coordinates, alpha = 1): 4th pick ties between indices 1 and 2; taking the
+    # higher index is a fork with deficit exactly 0, and the steps after it still follow its prefix
+    K = np.array([[0.0], [3.0], [7.0], [10.0], [5.0]])
+    rho = np.ones(5)
+    forks, pick, deficit = oracle.select_verify(K, rho, 5, 1.0, np.array([0, 3, 4, 2, 1], dtype=np.int32))
+    assert forks == 1 and pick.tolist() == [0, 3, 4, 1, 1] and deficit.tolist() == [0.0] * 5
+    # a wrong first landmark at alpha = 1 (every score equals alpha there): deficit 0, pick 0
+    forks, pick, deficit = oracle.select_verify(K, rho, 3, 1.0, np.array([2, 0, 3], dtype=np.int32))
+    want_pick, want_def = verify_from_definition(K, rho.min() / rho, 1.0, [2, 0, 3])
+    assert pick.tolist() == want_pick and np.allclose(deficit, want_def, atol=1e-15) and forks == 2
+    # density only (alpha = 0): best score 1 at the minimum-density point; candidate with u = 0.5
+    K = np.array([[0.0], [1.0], [2.0], [3.0]])
+    rho = np.array([0.2, 0.1, 0.4, 0.1])
+    forks, pick, deficit = oracle.select_verify(K, rho, 3, 0.0, np.array([0, 3, 1], dtype=np.int32))
+    assert forks == 2 and pick.tolist() == [1, 1, 1] and np.allclose(deficit, [0.5, 0.0, 0.0], atol=1e-15)
+
+
 # ------------------------------------------------------------------- gather
 def test_gather_is_bit_copy(oracle):
     rng = np.random.default_rng(31)
