@@ -86,7 +86,7 @@ hipError_t launch_gate(const void *hmain, const void *T, bool bf16, int N, int d
     const int es = bf16 ? 2 : 4;
     const bool wide = ((size_t)dm * es) % 16 == 0 && (reinterpret_cast<uintptr_t>(hmain) & 15) == 0 &&
                       (reinterpret_cast<uintptr_t>(T) & 15) == 0;
-    const dim3 grid((N + 3) / 4), block(256);
+    const dim3 grid((unsigned)(((long long)N + 3) / 4)), block(256);
     if (bf16)
         hipLaunchKernelGGL(gate_rows<true>, grid, block, 0, st, hmain, T, N, dm, theta, score, accept, wide ? 1 : 0);
     else
