@@ -107,7 +107,7 @@ def main() -> int:
         ws.ws_synapse_density(K, sig_list, rho=rho, workspace=ws_density)
         if ev:
             ev[1].record()
-        ws.ws_synapse_select(K, rho, w.k, w.alpha, idx=idx, workspace=ws_select)
+        ws.ws_synapse_select(K, rho, w.k, w.alpha, idx=idx, workspace=ws_select, check=False)
         if ev:
             ev[2].record()
         ws.ws_synapse_gather(K, V, idx, Ks=Ks, Vs=Vs)

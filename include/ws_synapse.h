@@ -18,9 +18,10 @@
  *   - K, V, Q, Ks, Vs must be 16-byte aligned; d must be 64 or 128.
  *   - The caller owns every buffer, including the workspace (size from
  *     ws_synapse_workspace_bytes, 256-byte aligned).  The library allocates nothing,
- *     keeps no state between calls and never synchronises the host: all work is
- *     enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream),
- *     so a caller can run the producer on one stream and the agents on others
+ *     keeps no state between calls, reads no environment variable and never synchronises
+ *     the host (ws_synapse_select_failed, which reads a flag back, is the one exception):
+ *     all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream), so a caller can run the producer on one stream and the agents on others
  *     (Sec. 3.1).  Two calls that share a workspace must be ordered by the caller.
  *   - Errors are return codes only.  Arguments are validated on the host before any
  *     launch; on an error nothing has been enqueued.  Non-finite inputs give
@@ -39,18 +40,22 @@ extern "C" {
 typedef enum {
     WS_OK = 0,
     WS_ERR_INVALID_ARG = 1,  /* NULL pointer, size < 1, k > L, alpha outside [0,1], sigma <= 0, misalignment */
-    WS_ERR_UNSUPPORTED = 2,  /* d not in {64,128}, unknown dtype, L >= 2^24 */
+    WS_ERR_UNSUPPORTED = 2,  /* d not in {64,128}, unknown dtype, L >= 2^24, a kernel that does not fit was named */
     WS_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or smaller than ws_synapse_workspace_bytes() */
-    WS_ERR_HIP = 4           /* a HIP call or kernel launch failed; see hipGetLastError() */
+    WS_ERR_HIP = 4,          /* a HIP call or kernel launch failed; see hipGetLastError() */
+    WS_STATUS_INT_RANGE = 0x7fffffff   /* not a status: gives the type the range of int (see below) */
 } ws_status;
 
-typedef enum { WS_F32 = 0, WS_BF16 = 1 } ws_dtype;
+/* Every enum of this header ends in such an enumerator, so that any int a caller passes is a value of the
+ * type and reaches the library's own checks (an unknown dtype or op is answered with an error code). */
+typedef enum { WS_F32 = 0, WS_BF16 = 1, WS_DTYPE_INT_RANGE = 0x7fffffff } ws_dtype;
 
 typedef enum {
     WS_OP_DENSITY = 0, WS_OP_SELECT = 1, WS_OP_GATHER = 2, WS_OP_ATTEND = 3,
     WS_OP_ATTENTION_MASS = 4,  /* H = G*Hkv heads, Hq = query heads per group times G */
     WS_OP_DENSITY_APPEND = 5,  /* k = m appended rows */
-    WS_OP_INJECT = 6           /* k = m injected rows */
+    WS_OP_INJECT = 6,          /* k = m injected rows */
+    WS_OP_INT_RANGE = 0x7fffffff
 } ws_op;
 
 typedef void *ws_stream; /* hipStream_t */
@@ -80,17 +85,66 @@ ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d,
  *   k         landmarks per head, 1 <= k <= L;  alpha in [0,1] (1 = coverage only)
  *   idx       dev [H,k] int32, written in pick order
  *   score_out dev [H,k] fp32 winning score per step, or NULL
+ *
  * Two kernels implement this call: one keeps a head's keys resident in registers and LDS for all
  * k steps (bf16 keys, heads that fit on chip), one streams them from memory every step (any size).
- * The library picks; the environment variable WS_SYNAPSE_SELECT=stream|resident forces one
- * (resident fails with WS_ERR_HIP when the sizes do not fit).  Both are persistent and their waves
- * wait on each other with a bounded spin; should a wait ever expire, the remaining entries of idx
- * for the affected heads are written as -1.
+ * ws_synapse_select lets the library pick; ws_synapse_select_with names one.
+ *
+ * Co-residency contract.  Both kernels are persistent: the workgroups that share a head exchange
+ * their partial maxima every step and wait for each other, so the WHOLE grid has to be resident on
+ * the device at once.  The launch is sized from the current device (its compute-unit count and the
+ * number of workgroups of the kernel a compute unit holds, both asked of the runtime at every call),
+ * which guarantees this when the selection has the device to itself.  The paper runs the producer
+ * beside other streams (Sec. 3.1, Sec. 4); work on other streams that holds compute units while a
+ * selection starts (a second selection in particular: AT MOST ONE SELECTION MAY BE IN FLIGHT PER
+ * DEVICE) can keep part of the grid from becoming resident.  Short kernels only delay it: every wait
+ * is a bounded spin of a few seconds.  If a wait does expire the kernel gives up cleanly: it sets the
+ * failure flag, writes -1 into the entries of idx it still owes for the affected heads, and drains.
+ * The call has long returned WS_OK by then, so the flag is the only report:
+ *   - the first 256 bytes of the selection workspace are the flag block; the int32 at offset 0 is 0
+ *     after a complete selection and 1 after one that gave up (it is reset by every call);
+ *   - ws_synapse_select_failed copies it to the host after synchronising the stream;
+ *   - ws_synapse_gather clamps a -1 to row 0 rather than following it, so a caller that skips the
+ *     check gets a wrong synapse, never a fault.
  */
 ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d,
                             const float *rho, int k, float alpha,
                             int32_t *idx, float *score_out,
                             void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/* The same step with the kernel named by the caller (tests and profiles; results are identical).
+ * WS_SELECT_RESIDENT returns WS_ERR_UNSUPPORTED when no resident instance fits the sizes on the
+ * current device (fp32 keys, heads too long to sit on chip). */
+typedef enum {
+    WS_SELECT_AUTO = 0, WS_SELECT_STREAMING = 1, WS_SELECT_RESIDENT = 2, WS_SELECT_INT_RANGE = 0x7fffffff
+} ws_select_kernel;
+ws_status ws_synapse_select_with(ws_select_kernel which, const void *K, ws_dtype dt, int H, int L, int d,
+                                 const float *rho, int k, float alpha,
+                                 int32_t *idx, float *score_out,
+                                 void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/* Did the last selection enqueued on `stream` with this workspace give up (see the co-residency
+ * contract above)?  Waits for the stream, then writes 0 or 1 to *failed (host).  This is the one
+ * call of the library that synchronises the host. */
+ws_status ws_synapse_select_failed(const void *workspace, ws_stream stream, int *failed);
+
+/* How a selection of these sizes is launched: which kernel, how many heads are in flight at once,
+ * how many workgroups share a head.  compute_units = 0 and workgroups_per_cu = 0 ask the current
+ * device (256 and the kernels' design value where none is visible); other values answer for a
+ * device of that shape (capacity planning, tests).  heads_in_flight * workgroups_per_head never
+ * exceeds compute_units * workgroups per unit.  WS_ERR_UNSUPPORTED: `which` names the resident
+ * kernel and no instance fits. */
+typedef struct {
+    int resident;             /* 1 = keys resident on chip, 0 = streaming */
+    int heads_in_flight;
+    int workgroups_per_head;
+    int threads;              /* per workgroup */
+    int rows_in_registers;    /* resident kernel: key rows per lane held in registers ... */
+    int rows_in_lds;          /* ... and in LDS */
+    int compute_units;        /* the device shape the plan was made for */
+} ws_select_plan;
+ws_status ws_synapse_select_plan(ws_select_kernel which, ws_dtype dt, int H, int L, int d,
+                                 int compute_units, int workgroups_per_cu, ws_select_plan *plan);
 
 /*
  * Fill the synapse buffer (Sec. 3.3, "a shared memory buffer containing only Landmarks"):
@@ -177,8 +231,8 @@ ws_status ws_synapse_inject(void *Kc, void *Vc, ws_dtype dt, int H, int Lcap, in
                             const void *Knew, const void *Vnew, int m, const int32_t *pos, float base,
                             void *workspace, size_t workspace_bytes, ws_stream stream);
 
-/* Which selection kernel ws_synapse_select would run for these sizes right now (the environment
- * override included): 1 = keys resident on chip, 0 = streaming.  For reports and profiles. */
+/* Which selection kernel ws_synapse_select would run for these sizes on the current device:
+ * 1 = keys resident on chip, 0 = streaming.  For reports and profiles. */
 int ws_synapse_select_is_resident(ws_dtype dt, int H, int L, int d);
 
 /* Bytes of workspace the given operation needs for these sizes (0 if none).  Arguments an

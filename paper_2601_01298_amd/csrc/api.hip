@@ -54,6 +54,7 @@ size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, in
     case WS_OP_INJECT:
         if (k < 1) return (size_t)-1;
         return ws::inject_workspace_bytes(d, k);
+    case WS_OP_INT_RANGE: break;
     }
     return (size_t)-1;
 }
@@ -77,9 +78,10 @@ ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d, co
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
 
-ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d, const float *rho, int k, float alpha,
-                            int32_t *idx, float *score_out, void *workspace, size_t workspace_bytes,
-                            ws_stream stream)
+namespace {
+
+ws_status check_select_args(const void *K, ws_dtype dt, int H, int L, int d, const float *rho, int k, float alpha,
+                            const int32_t *idx)
 {
     ws_status s = check_common(dt, d);
     if (s != WS_OK) return s;
@@ -87,11 +89,68 @@ ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d, con
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return WS_ERR_INVALID_ARG;
     if (L >= kMaxL) return WS_ERR_UNSUPPORTED;
     if (!aligned(K, 16) || !aligned(rho, 4) || !aligned(idx, 4)) return WS_ERR_INVALID_ARG;
+    return WS_OK;
+}
+
+}  // namespace
+
+ws_status ws_synapse_select_with(ws_select_kernel which, const void *K, ws_dtype dt, int H, int L, int d,
+                                 const float *rho, int k, float alpha, int32_t *idx, float *score_out,
+                                 void *workspace, size_t workspace_bytes, ws_stream stream)
+{
+    if (which != WS_SELECT_AUTO && which != WS_SELECT_STREAMING && which != WS_SELECT_RESIDENT) return WS_ERR_INVALID_ARG;
+    ws_status s = check_select_args(K, dt, H, L, d, rho, k, alpha, idx);
+    if (s != WS_OK) return s;
     s = check_ws(workspace, workspace_bytes, ws::select_workspace_bytes(H, L, d, dt == WS_BF16));
     if (s != WS_OK) return s;
-    const hipError_t e = ws::launch_select(K, dt == WS_BF16, H, L, d, rho, k, alpha, idx, score_out, workspace,
+    ws::SelectChoice c;
+    if (!ws::choose_select((int)which, dt == WS_BF16, H, L, d, ws::current_chip(), 0, c)) return WS_ERR_UNSUPPORTED;
+    const hipError_t e = ws::launch_select(c, K, dt == WS_BF16, H, L, d, rho, k, alpha, idx, score_out, workspace,
                                            (hipStream_t)stream);
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d, const float *rho, int k, float alpha,
+                            int32_t *idx, float *score_out, void *workspace, size_t workspace_bytes,
+                            ws_stream stream)
+{
+    return ws_synapse_select_with(WS_SELECT_AUTO, K, dt, H, L, d, rho, k, alpha, idx, score_out, workspace,
+                                  workspace_bytes, stream);
+}
+
+ws_status ws_synapse_select_failed(const void *workspace, ws_stream stream, int *failed)
+{
+    if (!failed) return WS_ERR_INVALID_ARG;
+    if (!workspace) return WS_ERR_INVALID_ARG;
+    const void *src = workspace;
+    int flag = 0;
+    if (hipMemcpyAsync(&flag, src, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess) return WS_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return WS_ERR_HIP;
+    *failed = flag != 0;
+    return WS_OK;
+}
+
+ws_status ws_synapse_select_plan(ws_select_kernel which, ws_dtype dt, int H, int L, int d, int compute_units,
+                                 int workgroups_per_cu, ws_select_plan *plan)
+{
+    if (which != WS_SELECT_AUTO && which != WS_SELECT_STREAMING && which != WS_SELECT_RESIDENT) return WS_ERR_INVALID_ARG;
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!plan || H < 1 || L < 1 || compute_units < 0 || workgroups_per_cu < 0) return WS_ERR_INVALID_ARG;
+    if (L >= kMaxL) return WS_ERR_UNSUPPORTED;
+    ws::Chip chip = ws::current_chip();
+    if (compute_units > 0) chip.cus = compute_units;
+    chip.wg_per_cu = workgroups_per_cu;
+    ws::SelectChoice c;
+    if (!ws::choose_select((int)which, dt == WS_BF16, H, L, d, chip, 0, c)) return WS_ERR_UNSUPPORTED;
+    plan->resident = c.resident ? 1 : 0;
+    plan->heads_in_flight = c.resident ? c.res.groups : c.stream.groups;
+    plan->workgroups_per_head = c.resident ? c.res.wgpg : c.stream.members;
+    plan->threads = c.resident ? 256 : c.stream.threads;
+    plan->rows_in_registers = c.resident ? c.res.rreg : 0;
+    plan->rows_in_lds = c.resident ? c.res.rlds : 0;
+    plan->compute_units = chip.cus;
+    return WS_OK;
 }
 
 ws_status ws_synapse_gather(const void *K, const void *V, ws_dtype dt, int H, int L, int d, const int32_t *idx, int k,
@@ -171,7 +230,7 @@ ws_status ws_synapse_gate(const void *h_main, const void *T, ws_dtype dt, int N,
     if (!h_main || !T || !score || !accept || N < 1 || dm < 1 || std::isnan(theta)) return WS_ERR_INVALID_ARG;
     const size_t es = dt == WS_BF16 ? 2 : 4;
     if (!aligned(h_main, es) || !aligned(T, es) || !aligned(score, 4) || !aligned(accept, 4)) return WS_ERR_INVALID_ARG;
-    if ((long long)(N + 3) / 4 > 0x7FFFFFFFLL) return WS_ERR_UNSUPPORTED;
+    if (((long long)N + 3) / 4 > 0x7FFFFFFFLL) return WS_ERR_UNSUPPORTED;
     const hipError_t e = ws::launch_gate(h_main, T, dt == WS_BF16, N, dm, theta, score, accept, (hipStream_t)stream);
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
@@ -196,8 +255,9 @@ ws_status ws_synapse_inject(void *Kc, void *Vc, ws_dtype dt, int H, int Lcap, in
 
 int ws_synapse_select_is_resident(ws_dtype dt, int H, int L, int d)
 {
-    if (check_common(dt, d) != WS_OK || H < 1 || L < 1) return 0;
-    return ws::select_uses_resident(H, L, d, dt == WS_BF16) ? 1 : 0;
+    ws_select_plan p;
+    if (ws_synapse_select_plan(WS_SELECT_AUTO, dt, H, L, d, 0, 0, &p) != WS_OK) return 0;
+    return p.resident;
 }
 
 const char *ws_status_string(ws_status s)
@@ -208,6 +268,7 @@ const char *ws_status_string(ws_status s)
     case WS_ERR_UNSUPPORTED: return "unsupported size or dtype";
     case WS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case WS_ERR_HIP: return "HIP runtime or launch failure";
+    case WS_STATUS_INT_RANGE: break;
     }
     return "unknown status";
 }

@@ -16,7 +16,6 @@
 // memory.  Every word carries an 8-bit sequence tag, slots are double-buffered by exchange
 // parity, and every wait is bounded: if it expires the group flags the failure, writes -1 into
 // the index entries it still owes and leaves, so the grid always drains.
-#include <cstdlib>
 
 #include "ws_internal.h"
 
@@ -287,7 +286,7 @@ __global__ void select_clear(unsigned long long *slots, int n, int *fail)
 }
 
 struct WsLayout {
-    size_t slots, fail, D, U, total;
+    size_t slots, D, U, total;
     int Lslab;
 };
 
@@ -295,76 +294,116 @@ WsLayout layout(const SelectPlan &p, int L)
 {
     WsLayout w;
     w.Lslab = (int)round_up((size_t)L, 64);
-    w.slots = 0;
-    w.fail = round_up((size_t)p.groups * 2 * kMaxMembers * sizeof(unsigned long long), 256);
-    w.D = w.fail + 256;
+    w.slots = kSelectFlagBytes;       // the failure flag sits in front
+    w.D = w.slots + round_up((size_t)p.groups * 2 * kMaxMembers * sizeof(unsigned long long), 256);
     w.U = w.D + round_up((size_t)p.groups * w.Lslab * sizeof(float), 256);
     w.total = w.U + round_up((size_t)p.groups * w.Lslab * sizeof(float), 256);
     return w;
 }
 
-}  // namespace
-
-// How a launch is shaped.  The chip has 256 compute units in 8 dies; a group's members must all
-// be resident at once (they wait on each other), so groups * members never exceeds 256 * 2
-// workgroups of 512 threads.  Few heads -> many members per head; many heads -> one die-local
-// group per head slot and the heads are walked through in rounds.
-SelectPlan select_plan(int H, int L, int d, bool bf16)
-{
-    (void)d;
-    (void)bf16;
-    SelectPlan p;
-    p.threads = 512;
-    const int max_wg = 512;
-    int groups = H < 32 ? H : 32;
-    if (groups >= 8) groups -= groups % 8;
-    int members = max_wg / groups;
-    int m2 = 1;
-    while (m2 * 2 <= members && m2 * 2 <= kMaxMembers) m2 *= 2;
-    // no point in slices smaller than one sweep iteration per member
-    while (m2 > 1 && (L + m2 - 1) / m2 < 256) m2 /= 2;
-    p.groups = groups;
-    p.members = m2;
-    return p;
-}
-
-size_t select_workspace_bytes(int H, int L, int d, bool bf16)
-{
-    // large enough for either kernel, so the choice can be made (or forced) at call time
-    size_t n = layout(select_plan(H, L, d, bf16), L).total;
-    if (resident_select_supported(H, L, d, bf16)) {
-        const size_t r = resident_select_workspace_bytes(H, L, d);
-        if (r > n) n = r;
-    }
-    return n;
-}
-
 template <typename T, int D>
-static hipError_t run_select(const SelArgs &a, const SelectPlan &p, hipStream_t st)
+hipError_t run_select(const SelArgs &a, const SelectPlan &p, hipStream_t st)
 {
     hipLaunchKernelGGL((select_stream<T, D, 512>), dim3(p.groups * p.members), dim3(512), 0, st, a);
     return hipGetLastError();
 }
 
-// Keys that fit on chip are selected by the resident kernel; the environment variable
-// WS_SYNAPSE_SELECT=stream|resident overrides the choice (testing, profiling).
-bool select_uses_resident(int H, int L, int d, bool bf16)
+// Workgroups of the streaming kernel a compute unit holds at once (two where there is no device to ask).
+int stream_occupancy()
 {
-    const char *force = getenv("WS_SYNAPSE_SELECT");
-    if (force && force[0] == 's') return false;
-    return resident_select_supported(H, L, d, bf16);
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_stream<uint16_t, 128, 512>, 512, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return 2;
+    }
+    return n;
 }
 
-hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k, float alpha,
-                         int32_t *idx, float *score_out, void *ws, hipStream_t st)
-{
-    const bool can_res = resident_select_supported(H, L, d, bf16);
-    const char *force = getenv("WS_SYNAPSE_SELECT");
-    if (force && force[0] == 'r' && !can_res) return hipErrorInvalidValue;
-    const bool use_res = select_uses_resident(H, L, d, bf16);
-    if (use_res) return launch_select_resident(K, H, L, d, rho, k, alpha, idx, score_out, ws, st);
+}  // namespace
 
-    const SelectPlan p = select_plan(H, L, d, bf16);
+Chip current_chip()
+{
+    Chip c{256, 0};
+    int dev = -1, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        c.cus = cus;
+    else
+        (void)hipGetLastError();
+    return c;
+}
+
+// How a launch of the streaming kernel is shaped.  A group's members wait on each other, so the whole
+// grid must be resident at once: groups * members never exceeds compute units x workgroups per unit.
+// Few heads -> many members per head; many heads -> the heads are walked through in rounds.
+SelectPlan select_plan(int H, int L, const Chip &chip, size_t slab_budget)
+{
+    SelectPlan p;
+    p.threads = 512;
+    const int occ = chip.wg_per_cu > 0 ? chip.wg_per_cu : stream_occupancy();
+    long long max_wg = (long long)chip.cus * occ;
+    if (max_wg < 1) max_wg = 1;
+    int groups = H < kMaxStreamGroups ? H : kMaxStreamGroups;
+    if (groups > max_wg) groups = (int)max_wg;
+    if (slab_budget > 0) {
+        const size_t per_group = 2 * round_up(round_up((size_t)L, 64) * sizeof(float), 256);
+        const size_t fit = slab_budget / per_group;
+        if (fit < (size_t)groups) groups = (int)fit;       // 0: the slabs of one head do not fit
+    }
+    if (groups >= 8) groups -= groups % 8;
+    int m2 = 1;
+    if (groups > 0) {
+        const long long members = max_wg / groups;
+        while (m2 * 2 <= members && m2 * 2 <= kMaxMembers) m2 *= 2;
+        // no point in slices smaller than one sweep iteration per member
+        while (m2 > 1 && (L + m2 - 1) / m2 < 256) m2 /= 2;
+    }
+    p.groups = groups;
+    p.members = m2;
+    return p;
+}
+
+size_t stream_select_workspace_bytes(const SelectPlan &p, int L) { return layout(p, L).total; }
+
+size_t select_workspace_bytes(int H, int L, int d, bool bf16)
+{
+    // Large enough for either kernel on any chip, so that the size does not depend on the device that
+    // happens to be current when it is asked for: the streaming kernel at its largest number of heads in
+    // flight, the resident one with a slot block for every head.
+    (void)d;
+    SelectPlan p;
+    p.groups = H < kMaxStreamGroups ? H : kMaxStreamGroups;
+    p.members = 1;
+    p.threads = 512;
+    size_t n = layout(p, L).total;
+    if (bf16) {
+        const size_t r = resident_select_workspace_bytes(H);
+        if (r > n) n = r;
+    }
+    return n;
+}
+
+bool choose_select(int which, bool bf16, int H, int L, int d, const Chip &chip, size_t slab_budget, SelectChoice &c)
+{
+    c.resident = false;
+    c.res = ResidentShape{0, 0, 0, 0, 0};
+    c.stream = SelectPlan{0, 0, 0};
+    const bool can_res = bf16 && which != 1 && resident_select_shape(H, L, d, chip, c.res);
+    if (which == 2 && !can_res) return false;
+    c.resident = can_res;
+    if (!c.resident) {
+        c.stream = select_plan(H, L, chip, slab_budget);
+        if (c.stream.groups < 1) return false;
+    }
+    return true;
+}
+
+hipError_t launch_select(const SelectChoice &c, const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
+                         float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st)
+{
+    if (c.resident) return launch_select_resident(K, H, L, d, rho, k, alpha, idx, score_out, ws, c.res, st);
+
+    const SelectPlan &p = c.stream;
     const WsLayout w = layout(p, L);
     char *base = reinterpret_cast<char *>(ws);
     SelArgs a;
@@ -372,8 +411,8 @@ hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const fl
     a.rho = rho;
     a.idx = idx;
     a.score_out = score_out;
+    a.fail = reinterpret_cast<int *>(base);
     a.slots = reinterpret_cast<unsigned long long *>(base + w.slots);
-    a.fail = reinterpret_cast<int *>(base + w.fail);
     a.Dws = reinterpret_cast<float *>(base + w.D);
     a.Uws = reinterpret_cast<float *>(base + w.U);
     a.H = H;

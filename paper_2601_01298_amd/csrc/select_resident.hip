@@ -30,79 +30,13 @@
 // channel small matters more than saving a barrier).  Waits are bounded; a workgroup whose wait
 // expires raises the failure flag, and (if it is the head's writer) writes -1 into the index entries
 // still owed, then leaves.
-#include "ws_internal.h"
+#include "select_resident_common.h"
 
 namespace ws {
 
 namespace {
 
-constexpr int kMaxMembers = 32;             // workgroups cooperating on one head
-constexpr unsigned kSpinLimit = 1u << 22;
-
-struct ResArgs {
-    const uint16_t *K;
-    const float *rho;
-    int32_t *idx;
-    float *score_out;
-    unsigned long long *slots;   // [groups][2 phases][2 kinds][kMaxMembers]
-    int *fail;
-    int H, L, k;
-    int groups, wgpg;            // heads in flight, workgroups per head
-    float alpha;
-};
-
-// ---- wave-wide unsigned max via DPP: 4 in-row steps, then one lane of each 16-lane row ------
-template <int CTRL>
-__device__ __forceinline__ unsigned dpp_umax(unsigned v)
-{
-    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
-    return o > v ? o : v;
-}
-
-__device__ __forceinline__ unsigned wave_umax(unsigned v)
-{
-    v = dpp_umax<0xB1>(v);    // quad_perm [1,0,3,2]
-    v = dpp_umax<0x4E>(v);    // quad_perm [2,3,0,1]
-    v = dpp_umax<0x141>(v);   // row_half_mirror
-    v = dpp_umax<0x140>(v);   // row_mirror
-    const unsigned a = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
-    const unsigned b = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
-    const unsigned c = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
-    const unsigned d = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
-    const unsigned ab = a > b ? a : b, cd = c > d ? c : d;
-    return ab > cd ? ab : cd;
-}
-
-// wave-wide float sum; every lane ends up with the same value
-template <int CTRL>
-__device__ __forceinline__ float dpp_fadd(float v)
-{
-    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-
-__device__ __forceinline__ float wave_fsum(float v)
-{
-    v = dpp_fadd<0xB1>(v);
-    v = dpp_fadd<0x4E>(v);
-    v = dpp_fadd<0x141>(v);
-    v = dpp_fadd<0x140>(v);
-    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-    return (a + b) + (c + d);
-}
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// Second half of a 64-bit maximum over the wave: `lo` of the lane whose first half matched.  Nearly
-// always exactly one lane matches, and then a ballot and one readlane replace the whole reduction.
-__device__ __forceinline__ unsigned wave_pick_lo(bool match, unsigned lo)
-{
-    const unsigned long long m = __ballot(match);
-    if (__popcll(m) == 1) return (unsigned)__builtin_amdgcn_readlane((int)lo, (int)__builtin_ctzll(m));
-    return wave_umax(match ? lo : 0u);
-}
+using namespace resident;
 
 struct Shared {
     unsigned dm[4], hi[4], lo[4];   // one entry per wave of the workgroup
@@ -651,36 +585,6 @@ __global__ void resident_clear(unsigned long long *slots, int n, int *fail)
     if (i == 0) *fail = 0;
 }
 
-struct Shape {
-    int rreg, rlds, wgpg, groups, rounds;
-};
-
-// Pick rows per lane and workgroups per head: fewest rounds over the heads, then fewest rows per
-// lane (more waves per head, less serial work per step).  512 workgroups of 256 threads are
-// co-resident (2 per compute unit at 256 VGPRs and <= 64 KB LDS each).
-bool pick_shape(int H, int L, int d, Shape &best)
-{
-    static const int opts64[][2] = {{1, 0}, {2, 0}, {4, 0}, {6, 2}};
-    static const int opts128[][2] = {{1, 0}, {2, 0}, {3, 1}};
-    const int(*opts)[2] = d == 64 ? opts64 : opts128;
-    const int nopts = d == 64 ? 4 : 3;
-    bool found = false;
-    for (int i = 0; i < nopts; ++i) {
-        const int R = opts[i][0] + opts[i][1];
-        const int wgpg = (L + 256 * R - 1) / (256 * R);
-        if (wgpg > kMaxMembers) continue;
-        int groups = 512 / wgpg;
-        if (groups > H) groups = H;
-        if (groups >= 8) groups -= groups % 8;
-        const int rounds = (H + groups - 1) / groups;
-        if (!found || rounds < best.rounds) {
-            best = Shape{opts[i][0], opts[i][1], wgpg, groups, rounds};
-            found = true;
-        }
-    }
-    return found;
-}
-
 template <int D, int RREG, int RLDS>
 hipError_t run(const ResArgs &a, hipStream_t st)
 {
@@ -688,34 +592,83 @@ hipError_t run(const ResArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-}  // namespace
+// Key rows per lane (in registers, in LDS) of the compiled instances.
+constexpr int kOpts64[][2] = {{1, 0}, {2, 0}, {4, 0}, {6, 2}};
+constexpr int kOpts128[][2] = {{1, 0}, {2, 0}, {3, 1}};
 
-bool resident_select_supported(int H, int L, int d, bool bf16)
+// Workgroups of one instance that a compute unit holds at once, asked of the runtime for the current
+// device (a host-side computation from the kernel's register and LDS use: no allocation, no launch).
+// Every instance is built for two; that is the answer where there is no device to ask.
+int instance_occupancy(int d, int rreg)
 {
-    Shape s;
-    return bf16 && (d == 64 || d == 128) && pick_shape(H, L, d, s);
+    int n = 0;
+    hipError_t e = hipErrorInvalidValue;
+    if (d == 64) {
+        if (rreg == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 1, 0>, 256, 0);
+        else if (rreg == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 2, 0>, 256, 0);
+        else if (rreg == 4) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 4, 0>, 256, 0);
+        else e = resident_ahead_occupancy(&n);
+    } else {
+        if (rreg == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 1, 0>, 256, 0);
+        else if (rreg == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 2, 0>, 256, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 3, 1>, 256, 0);
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return 2;
+    }
+    return n;
 }
 
-size_t resident_select_workspace_bytes(int H, int L, int d)
+}  // namespace
+
+// Rows per lane and workgroups per head: fewest rounds over the heads, then fewest rows per lane (more
+// waves per head, less serial work per step).  The workgroups of a head wait on each other, so the
+// whole grid must be resident at once: groups * wgpg never exceeds compute units x workgroups per unit.
+bool resident_select_shape(int H, int L, int d, const Chip &chip, ResidentShape &best)
 {
-    Shape s;
-    if (!pick_shape(H, L, d, s)) return 0;
-    return round_up((size_t)s.groups * 4 * kMaxMembers * sizeof(unsigned long long), 256) + 256;
+    if (d != 64 && d != 128) return false;
+    const int(*opts)[2] = d == 64 ? kOpts64 : kOpts128;
+    const int nopts = d == 64 ? 4 : 3;
+    bool found = false;
+    for (int i = 0; i < nopts; ++i) {
+        const int R = opts[i][0] + opts[i][1];
+        const int wgpg = (L + 256 * R - 1) / (256 * R);
+        if (wgpg > kMaxMembers) continue;
+        const int occ = chip.wg_per_cu > 0 ? chip.wg_per_cu : instance_occupancy(d, opts[i][0]);
+        const long long max_wg = (long long)chip.cus * occ;
+        if (wgpg > max_wg) continue;                   // the group of one head could not be resident
+        int groups = (int)(max_wg / wgpg);
+        if (groups > kMaxResidentGroups) groups = kMaxResidentGroups;
+        if (groups > H) groups = H;
+        if (groups >= 8) groups -= groups % 8;         // whole groups per die
+        const int rounds = (H + groups - 1) / groups;
+        if (!found || rounds < best.rounds) {
+            best = ResidentShape{opts[i][0], opts[i][1], wgpg, groups, rounds};
+            found = true;
+        }
+    }
+    return found;
+}
+
+size_t resident_select_workspace_bytes(int H)
+{
+    // the flag block, then four tagged slots per member for every head that can be in flight on any chip
+    const int groups = H < kMaxResidentGroups ? H : kMaxResidentGroups;
+    return kSelectFlagBytes + round_up((size_t)groups * 4 * kMaxMembers * sizeof(unsigned long long), 256);
 }
 
 hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
-                                  int32_t *idx, float *score_out, void *ws, hipStream_t st)
+                                  int32_t *idx, float *score_out, void *ws, const ResidentShape &s, hipStream_t st)
 {
-    Shape s;
-    if (!pick_shape(H, L, d, s)) return hipErrorInvalidValue;
     ResArgs a;
     a.K = reinterpret_cast<const uint16_t *>(K);
     a.rho = rho;
     a.idx = idx;
     a.score_out = score_out;
-    a.slots = reinterpret_cast<unsigned long long *>(ws);
+    a.fail = reinterpret_cast<int *>(ws);
+    a.slots = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(ws) + kSelectFlagBytes);
     const size_t nslots = (size_t)s.groups * 4 * kMaxMembers;
-    a.fail = reinterpret_cast<int *>(reinterpret_cast<char *>(ws) + round_up(nslots * sizeof(unsigned long long), 256));
     a.H = H;
     a.L = L;
     a.k = k;

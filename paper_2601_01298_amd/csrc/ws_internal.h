@@ -41,29 +41,58 @@ hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const f
                           float *rho, void *ws, hipStream_t st);
 
 // ---- selection -----------------------------------------------------------------------
+// What the selection kernels need to know about the chip they run on.  Both are persistent and their
+// workgroups wait on each other, so a launch may never hold more workgroups than the device keeps
+// resident at once: compute units x workgroups per unit.
+struct Chip {
+    int cus;         // compute units of the device
+    int wg_per_cu;   // workgroups per compute unit; 0 = ask the runtime for the kernel instance in question
+};
+// The current device, or the MI355X figure (256 compute units) where no device is visible.
+Chip current_chip();
+
+constexpr size_t kSelectFlagBytes = 256;    // head of every selection workspace: int32 failure flag at offset 0
+constexpr int kMaxResidentGroups = 1024;    // heads in flight the resident kernel's workspace is sized for
+constexpr int kMaxStreamGroups = 32;        // heads in flight of the streaming kernel
+
 struct SelectPlan {
     int groups;   // heads processed concurrently (each by `members` workgroups)
     int members;  // workgroups cooperating on one head
     int threads;  // threads per workgroup
 };
-SelectPlan select_plan(int H, int L, int d, bool bf16);
+// slab_budget: bytes the per-head distance and inverse-density slabs may take together (0 = no limit)
+SelectPlan select_plan(int H, int L, const Chip &chip, size_t slab_budget);
+size_t stream_select_workspace_bytes(const SelectPlan &p, int L);
 size_t select_workspace_bytes(int H, int L, int d, bool bf16);
-// the choice launch_select makes (environment override WS_SYNAPSE_SELECT included)
-bool select_uses_resident(int H, int L, int d, bool bf16);
-hipError_t launch_select(const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
-                         float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st);
 
-// register/LDS-resident variant (bf16, heads small enough to sit on chip)
-bool resident_select_supported(int H, int L, int d, bool bf16);
-size_t resident_select_workspace_bytes(int H, int L, int d);
+struct ResidentShape {
+    int rreg, rlds;   // key rows per lane in registers and in LDS
+    int wgpg;         // workgroups per head
+    int groups;       // heads in flight
+    int rounds;       // passes over the heads
+};
+// register/LDS-resident variant (bf16, heads small enough to sit on chip); false when no instance fits
+bool resident_select_shape(int H, int L, int d, const Chip &chip, ResidentShape &shape);
+size_t resident_select_workspace_bytes(int H);
 hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
-                                  int32_t *idx, float *score_out, void *ws, hipStream_t st);
+                                  int32_t *idx, float *score_out, void *ws, const ResidentShape &shape, hipStream_t st);
 // the same kernel with the next step's screen run during the exchange; d = 64 and eight rows per lane only,
 // called by launch_select_resident with the workspace laid out and cleared
 hipError_t launch_select_resident_ahead(const void *K, int H, int L, const float *rho, int k, float alpha, int32_t *idx,
                                         float *score_out, unsigned long long *slots, int *fail, int groups, int wgpg,
                                         hipStream_t st);
+hipError_t resident_ahead_occupancy(int *workgroups_per_cu);
 
+// which: 0 = the library chooses, 1 = streaming kernel, 2 = resident kernel
+struct SelectChoice {
+    bool resident;
+    SelectPlan stream;
+    ResidentShape res;
+};
+// false when `which` asks for the resident kernel and no instance fits these sizes on this chip
+bool choose_select(int which, bool bf16, int H, int L, int d, const Chip &chip, size_t slab_budget, SelectChoice &c);
+hipError_t launch_select(const SelectChoice &c, const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
+                         float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st);
 // ---- gather --------------------------------------------------------------------------
 hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int L,
                          const int32_t *idx, int k, void *Ks, void *Vs, hipStream_t st);

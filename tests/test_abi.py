@@ -84,6 +84,24 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, float("nan"), fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
     assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, None, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
     assert S(fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, fake, None, fake, 8, None) == b.WS_ERR_WORKSPACE
+    W = lib.ws_synapse_select_with
+    assert W(3, fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    assert W(b.WS_SELECT_STREAMING, fake, b.WS_BF16, 2, 100, 64, fake, 101, 0.5, fake, None, fake, 1 << 30, None) \
+        == b.WS_ERR_INVALID_ARG
+    assert W(b.WS_SELECT_RESIDENT, fake, b.WS_F32, 2, 100, 64, fake, 10, 0.5, fake, None, fake, 1 << 30, None) \
+        == b.WS_ERR_UNSUPPORTED                                               # fp32 keys have no on-chip kernel
+    assert W(b.WS_SELECT_RESIDENT, fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, fake, None, fake, 8, None) == b.WS_ERR_WORKSPACE
+    out = ctypes.c_int(7)
+    assert lib.ws_synapse_select_failed(None, None, ctypes.byref(out)) == b.WS_ERR_INVALID_ARG
+    assert lib.ws_synapse_select_failed(fake, None, None) == b.WS_ERR_INVALID_ARG
+    plan = b.SelectPlan()
+    P = lib.ws_synapse_select_plan
+    assert P(0, b.WS_BF16, 2, 100, 64, 0, 0, None) == b.WS_ERR_INVALID_ARG
+    assert P(0, b.WS_BF16, 0, 100, 64, 0, 0, ctypes.byref(plan)) == b.WS_ERR_INVALID_ARG
+    assert P(0, b.WS_BF16, 2, 100, 64, -1, 0, ctypes.byref(plan)) == b.WS_ERR_INVALID_ARG
+    assert P(9, b.WS_BF16, 2, 100, 64, 0, 0, ctypes.byref(plan)) == b.WS_ERR_INVALID_ARG
+    assert P(0, b.WS_BF16, 2, 100, 48, 0, 0, ctypes.byref(plan)) == b.WS_ERR_UNSUPPORTED
+    assert P(0, b.WS_BF16, 2, 100, 64, 0, 0, ctypes.byref(plan)) == b.WS_OK and plan.compute_units == 256
     G = lib.ws_synapse_gather
     assert G(fake, None, b.WS_BF16, 2, 100, 64, fake, 10, fake, fake, None) == b.WS_ERR_INVALID_ARG
     assert G(fake, fake, b.WS_BF16, 2, 100, 32, fake, 10, fake, fake, None) == b.WS_ERR_UNSUPPORTED
@@ -132,19 +150,70 @@ def test_bad_arguments_of_the_next_steps_are_rejected_on_the_host(lib):
     assert b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY_APPEND, b.WS_BF16, 8, 4096, 64) > 0
 
 
-def test_selection_kernel_choice_is_host_logic(lib, monkeypatch):
-    """Which selection kernel a shape gets is decided on the host from the sizes alone: heads whose keys fit
-    the chip's registers and LDS (32 headline heads at a time) stay on chip, fp32 keys and oversized heads stream."""
+def test_selection_kernel_choice_is_host_logic(lib):
+    """Which selection kernel a shape gets is decided on the host from the sizes and the device's shape: heads
+    whose keys fit the chip's registers and LDS (32 headline heads at a time) stay on chip, fp32 keys and
+    oversized heads stream.  No environment variable takes part."""
+    import subprocess
+    import sys
     from paper_2601_01298_amd import binding as b
     from paper_2601_01298_amd import synthetic as syn
-    monkeypatch.delenv("WS_SYNAPSE_SELECT", raising=False)
     expect = {1: False, 2: True, 3: True, 4: True, 5: False}
     for cfg, w in syn.WORKLOADS.items():
         dt = b.WS_BF16 if w.dtype == "bf16" else b.WS_F32
         assert b.ws_synapse_select_is_resident(dt, w.H, w.L, w.d) == expect[cfg], w.name
         assert b.ws_synapse_workspace_bytes(b.WS_OP_SELECT, dt, w.H, w.L, w.d, w.k) > 0
-    monkeypatch.setenv("WS_SYNAPSE_SELECT", "stream")
-    assert not b.ws_synapse_select_is_resident(b.WS_BF16, 384, 32768, 64)
+    assert not b.ws_synapse_select_plan("stream", b.WS_BF16, 384, 32768, 64).resident
+    with pytest.raises(b.WsError):
+        b.ws_synapse_select_plan("resident", b.WS_F32, 1, 512, 64)          # fp32 keys never sit on chip
+    with pytest.raises(b.WsError):
+        b.ws_synapse_select_plan("resident", b.WS_BF16, 8, 131072, 128)     # a head larger than 32 workgroups hold
+    code = ("import os; os.environ['WS_SYNAPSE_SELECT']='stream'; from paper_2601_01298_amd import binding as b; "
+            "print(int(b.ws_synapse_select_is_resident(b.WS_BF16, 384, 32768, 64)))")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT, timeout=120)
+    assert r.stdout.strip() == "1", r.stderr                                # the old switch is gone
+    assert "getenv" not in "".join(open(os.path.join(ROOT, "paper_2601_01298_amd", "csrc", f)).read()
+                                   for f in os.listdir(os.path.join(ROOT, "paper_2601_01298_amd", "csrc")))
+
+
+@pytest.mark.parametrize("cus", [32, 64, 128, 256, 304])
+@pytest.mark.parametrize("per_cu", [1, 2])
+def test_selection_grid_fits_the_device(lib, cus, per_cu):
+    """The selection kernels' workgroups wait on each other, so a launch must never exceed what the device
+    keeps resident at once (compute units x workgroups per unit), whatever the device's shape; and a head
+    needs all its keys covered: workgroups_per_head x rows x 256 >= L for the on-chip kernel."""
+    from paper_2601_01298_amd import binding as b
+    shapes = [(384, 32768, 64), (16, 4096, 64), (32, 8192, 128), (8, 131072, 128), (1, 512, 64), (1, 100, 128),
+              (1000, 2048, 64), (3, 70000, 64), (40, 4096, 64), (136, 4096, 64), (72, 4096, 128), (5, 16_000_000, 64)]
+    for kernel in ("auto", "stream", "resident"):
+        for dt in (b.WS_BF16, b.WS_F32):
+            for H, L, d in shapes:
+                try:
+                    p = b.ws_synapse_select_plan(kernel, dt, H, L, d, cus, per_cu)
+                except b.WsError as e:
+                    assert kernel == "resident" and e.status == b.WS_ERR_UNSUPPORTED
+                    continue
+                assert p.compute_units == cus
+                assert 1 <= p.heads_in_flight <= H and p.workgroups_per_head >= 1
+                assert p.heads_in_flight * p.workgroups_per_head <= cus * per_cu, (kernel, dt, H, L, d)
+                if p.resident:
+                    assert dt == b.WS_BF16 and kernel != "stream" and p.threads == 256
+                    assert p.workgroups_per_head * 256 * (p.rows_in_registers + p.rows_in_lds) >= L
+                    assert p.workgroups_per_head <= 32
+                else:
+                    assert kernel != "resident" and p.threads == 512 and p.workgroups_per_head <= 64
+    # the headline on the full chip: 32 heads in flight, 16 workgroups each, 6 + 2 rows per lane
+    p = b.ws_synapse_select_plan("auto", b.WS_BF16, 384, 32768, 64, 256, 2)
+    assert (p.resident, p.heads_in_flight, p.workgroups_per_head, p.rows_in_registers, p.rows_in_lds) == (1, 32, 16, 6, 2)
+    # a quarter of the chip still keeps a 32k-token head on chip, fewer at a time
+    p = b.ws_synapse_select_plan("auto", b.WS_BF16, 384, 32768, 64, 64, 2)
+    assert p.resident and p.heads_in_flight == 8
+    # a device too small for one head's group falls back to streaming
+    assert not b.ws_synapse_select_plan("auto", b.WS_BF16, 384, 32768, 64, 4, 2).resident
+
+
+def test_density_workspace_size(lib):
+    from paper_2601_01298_amd import binding as b
     # the density workspace: a 16-byte record per key, and column partial sums capped near 4 GiB however many heads
     a = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 384, 32768, 64)
     c = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 4096, 32768, 64)

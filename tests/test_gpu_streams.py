@@ -42,7 +42,7 @@ def test_producer_and_consumer_streams_with_two_synapse_buffers():
             rho = torch.empty((w.H, L), dtype=torch.float32, device=dev)
             ws.ws_synapse_density_append(K, m, sigma, rho_prev, rho_new=rho, workspace=wapp, stream=stream)
         idx = torch.empty((w.H, w.k), dtype=torch.int32, device=dev)
-        ws.ws_synapse_select(K, rho, w.k, w.alpha, idx=idx, workspace=wsel, stream=stream)
+        ws.ws_synapse_select(K, rho, w.k, w.alpha, idx=idx, workspace=wsel, stream=stream, check=False)
         ws.ws_synapse_gather(K, V, idx, Ks=Ks, Vs=Vs, stream=stream)
         return rho, idx
 
@@ -94,6 +94,7 @@ def test_producer_and_consumer_streams_with_two_synapse_buffers():
     got_O.append(O)
     torch.cuda.synchronize()
 
+    assert not ws.ws_synapse_select_failed(wsel)      # the flag block at the head of the selection workspace
     for s in range(steps + 1):
         assert int(got_idx[s].min()) >= 0
         assert torch.equal(got_idx[s], ref_idx[s]), f"step {s}: landmarks differ between the two schedules"
