@@ -43,6 +43,7 @@ typedef enum {
     WS_ERR_UNSUPPORTED = 2,  /* d not in {64,128}, unknown dtype, L >= 2^24, a kernel that does not fit was named */
     WS_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or smaller than ws_synapse_workspace_bytes() */
     WS_ERR_HIP = 4,          /* a HIP call or kernel launch failed; see hipGetLastError() */
+    WS_ERR_TOO_LARGE = 5,    /* ws_synapse_select_static only: the sizes need more than its fixed scratch */
     WS_STATUS_INT_RANGE = 0x7fffffff   /* not a status: gives the type the range of int (see below) */
 } ws_status;
 
@@ -123,9 +124,31 @@ ws_status ws_synapse_select_with(ws_select_kernel which, const void *K, ws_dtype
                                  int32_t *idx, float *score_out,
                                  void *workspace, size_t workspace_bytes, ws_stream stream);
 
+/*
+ * ws_synapse_select for callers that cannot allocate and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * same results as ws_synapse_select, but the scratch the kernels need (failure flag, exchange slots, and
+ * the streaming kernel's distance / inverse-density slabs) lives in a fixed array inside the library's
+ * device image: 256 bytes + 1 MiB + 4 MiB = 5 243 136 bytes per device, held until the process ends.
+ * The call allocates nothing (no hipMalloc, no hipFree, no allocating library routine) and clears what it
+ * needs with a small kernel on `stream`.
+ *   - Sizes whose scratch does not fit are refused with WS_ERR_TOO_LARGE before anything is enqueued.  The
+ *     on-chip kernel (bf16 heads that fit the chip: every size it serves) always fits; the streaming kernel
+ *     runs as many heads at once as fit 4 MiB of slabs (8 bytes per key and head in flight), and a single
+ *     head must fit: L <= 524 288.
+ *   - Every call on a device shares that device's array, which keeps the last call's contents: calls that
+ *     overlap on one device (two streams, two threads) race.  Order them, as with a shared workspace; the
+ *     one-selection-in-flight rule above applies anyway.
+ *   - ws_synapse_select_failed(NULL, stream, &failed) reads this array's failure flag on the current device.
+ */
+ws_status ws_synapse_select_static(const void *K, ws_dtype dt, int H, int L, int d,
+                                   const float *rho, int k, float alpha,
+                                   int32_t *idx, float *score_out, ws_stream stream);
+
 /* Did the last selection enqueued on `stream` with this workspace give up (see the co-residency
- * contract above)?  Waits for the stream, then writes 0 or 1 to *failed (host).  This is the one
- * call of the library that synchronises the host. */
+ * contract above)?  Waits for the stream, then writes 0 or 1 to *failed (host).  workspace == NULL
+ * means the fixed scratch of ws_synapse_select_static on the current device.  This is the one call of
+ * the library that synchronises the host. */
 ws_status ws_synapse_select_failed(const void *workspace, ws_stream stream, int *failed);
 
 /* How a selection of these sizes is launched: which kernel, how many heads are in flight at once,

@@ -12,7 +12,7 @@ import os
 
 import torch
 
-WS_OK, WS_ERR_INVALID_ARG, WS_ERR_UNSUPPORTED, WS_ERR_WORKSPACE, WS_ERR_HIP = range(5)
+WS_OK, WS_ERR_INVALID_ARG, WS_ERR_UNSUPPORTED, WS_ERR_WORKSPACE, WS_ERR_HIP, WS_ERR_TOO_LARGE = range(6)
 WS_F32, WS_BF16 = 0, 1
 WS_OP_DENSITY, WS_OP_SELECT, WS_OP_GATHER, WS_OP_ATTEND = range(4)
 WS_OP_ATTENTION_MASS, WS_OP_DENSITY_APPEND, WS_OP_INJECT = 4, 5, 6
@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.ws_synapse_select.restype = ci
         L.ws_synapse_select_with.argtypes = [ci, vp, ci, ci, ci, ci, vp, ci, cf, vp, vp, vp, sz, vp]
         L.ws_synapse_select_with.restype = ci
+        L.ws_synapse_select_static.argtypes = [vp, ci, ci, ci, ci, vp, ci, cf, vp, vp, vp]
+        L.ws_synapse_select_static.restype = ci
         L.ws_synapse_select_failed.argtypes = [vp, vp, ctypes.POINTER(ci)]
         L.ws_synapse_select_failed.restype = ci
         L.ws_synapse_select_plan.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(SelectPlan)]
@@ -206,11 +208,29 @@ def ws_synapse_select_with(kernel: str, K, rho, k, alpha, **kw):
     return ws_synapse_select(K, rho, k, alpha, kernel=kernel, **kw)
 
 
-def ws_synapse_select_failed(workspace: torch.Tensor, stream=None) -> bool:
-    """Waits for the stream, then reports whether the last selection on this workspace gave up."""
+def ws_synapse_select_static(K: torch.Tensor, rho: torch.Tensor, k: int, alpha: float, idx: torch.Tensor,
+                             score_out: torch.Tensor | None = None, stream=None):
+    """ws_synapse_select on the library's own fixed scratch: nothing is allocated here or in the library, so
+    the caller supplies idx [H,k] int32 (and score_out [H,k] fp32 if wanted)."""
+    _dev(K, "K")
+    H, L, d = K.shape
+    dt = _dtype_code(K)
+    _want(rho, "rho", (H, L), torch.float32)
+    _want(idx, "idx", (H, k), torch.int32)
+    if score_out is not None:
+        _want(score_out, "score_out", (H, k), torch.float32)
+    _check(lib().ws_synapse_select_static(K.data_ptr(), dt, H, L, d, rho.data_ptr(), int(k), float(alpha), idx.data_ptr(),
+                                          score_out.data_ptr() if score_out is not None else None, _stream(stream)),
+           "ws_synapse_select_static")
+    return idx
+
+
+def ws_synapse_select_failed(workspace: torch.Tensor | None, stream=None) -> bool:
+    """Waits for the stream, then reports whether the last selection on this workspace gave up
+    (workspace None: the fixed scratch of ws_synapse_select_static)."""
     out = ctypes.c_int(0)
-    _check(lib().ws_synapse_select_failed(_dev(workspace, "workspace").data_ptr(), _stream(stream), ctypes.byref(out)),
-           "ws_synapse_select_failed")
+    ptr = _dev(workspace, "workspace").data_ptr() if workspace is not None else None
+    _check(lib().ws_synapse_select_failed(ptr, _stream(stream), ctypes.byref(out)), "ws_synapse_select_failed")
     return bool(out.value)
 
 

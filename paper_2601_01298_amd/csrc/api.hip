@@ -118,11 +118,32 @@ ws_status ws_synapse_select(const void *K, ws_dtype dt, int H, int L, int d, con
                                   workspace_bytes, stream);
 }
 
+ws_status ws_synapse_select_static(const void *K, ws_dtype dt, int H, int L, int d, const float *rho, int k,
+                                   float alpha, int32_t *idx, float *score_out, ws_stream stream)
+{
+    ws_status s = check_select_args(K, dt, H, L, d, rho, k, alpha, idx);
+    if (s != WS_OK) return s;
+    ws::SelectChoice c;
+    if (!ws::choose_select(0, dt == WS_BF16, H, L, d, ws::current_chip(), ws::kStaticSlabBytes, c)) return WS_ERR_TOO_LARGE;
+    const size_t need = c.resident ? ws::resident_select_workspace_bytes(c.res.groups)
+                                   : ws::stream_select_workspace_bytes(c.stream, L);
+    if (need > ws::kStaticScratchBytes) return WS_ERR_TOO_LARGE;
+    void *scratch_ptr = nullptr;
+    if (ws::select_static_scratch(&scratch_ptr) != hipSuccess) return WS_ERR_HIP;
+    const hipError_t e = ws::launch_select(c, K, dt == WS_BF16, H, L, d, rho, k, alpha, idx, score_out, scratch_ptr,
+                                           (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
 ws_status ws_synapse_select_failed(const void *workspace, ws_stream stream, int *failed)
 {
     if (!failed) return WS_ERR_INVALID_ARG;
-    if (!workspace) return WS_ERR_INVALID_ARG;
     const void *src = workspace;
+    if (!src) {
+        void *p = nullptr;
+        if (ws::select_static_scratch(&p) != hipSuccess) return WS_ERR_HIP;
+        src = p;
+    }
     int flag = 0;
     if (hipMemcpyAsync(&flag, src, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess) return WS_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return WS_ERR_HIP;
@@ -268,6 +289,7 @@ const char *ws_status_string(ws_status s)
     case WS_ERR_UNSUPPORTED: return "unsupported size or dtype";
     case WS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case WS_ERR_HIP: return "HIP runtime or launch failure";
+    case WS_ERR_TOO_LARGE: return "sizes exceed the fixed scratch of the entry point that allocates nothing";
     case WS_STATUS_INT_RANGE: break;
     }
     return "unknown status";

@@ -16,6 +16,7 @@
 // memory.  Every word carries an 8-bit sequence tag, slots are double-buffered by exchange
 // parity, and every wait is bounded: if it expires the group flags the failure, writes -1 into
 // the index entries it still owes and leaves, so the grid always drains.
+#include <atomic>
 
 #include "ws_internal.h"
 
@@ -319,7 +320,31 @@ int stream_occupancy()
     return n;
 }
 
+// Scratch of the entry point that allocates nothing.  In host code this name is only a handle: the
+// address of a device's copy comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_of_device[kMaxDevices];
+
 }  // namespace
+
+hipError_t select_static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = scratch_of_device[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        scratch_of_device[dev].store(p, std::memory_order_release);     // every thread would store the same address
+    }
+    *ptr = p;
+    return hipSuccess;
+}
 
 Chip current_chip()
 {

@@ -93,6 +93,11 @@ struct SelectChoice {
 bool choose_select(int which, bool bf16, int H, int L, int d, const Chip &chip, size_t slab_budget, SelectChoice &c);
 hipError_t launch_select(const SelectChoice &c, const void *K, bool bf16, int H, int L, int d, const float *rho, int k,
                          float alpha, int32_t *idx, float *score_out, void *ws, hipStream_t st);
+// The no-allocation variant's scratch: a fixed array in device memory, one copy per device.
+constexpr size_t kStaticSlabBytes = (size_t)4 << 20;       // distance + inverse-density slabs of the streaming kernel
+constexpr size_t kStaticScratchBytes = kSelectFlagBytes + ((size_t)1 << 20) + kStaticSlabBytes;
+hipError_t select_static_scratch(void **ptr);              // address of the current device's copy
+
 // ---- gather --------------------------------------------------------------------------
 hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int L,
                          const int32_t *idx, int k, void *Ks, void *Vs, hipStream_t st);

@@ -53,7 +53,10 @@ int main(void)
     CHECK(ws_synapse_select_plan(WS_SELECT_AUTO, WS_BF16, H, 1000, 64, 64, 2, NULL) == WS_ERR_INVALID_ARG);
     CHECK(ws_synapse_select_plan(WS_SELECT_RESIDENT, WS_BF16, H, 100000, 64, 0, 0, &plan) == WS_ERR_UNSUPPORTED);
     int failed = -1;
-    CHECK(ws_synapse_select_failed(NULL, NULL, &failed) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_select_failed(NULL, NULL, &failed) == WS_ERR_HIP);      /* no device here: no static scratch */
+    CHECK(ws_synapse_select_static(fake, WS_BF16, H, 1000, 64, fake, 1001, 0.5f, fake, NULL, NULL) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_select_static(fake, WS_F32, H, 2000000, 64, fake, 20, 0.5f, fake, NULL, NULL) == WS_ERR_TOO_LARGE);
+    CHECK(ws_synapse_select_static(fake, WS_BF16, H, 1000, 64, fake, 20, 0.5f, fake, NULL, NULL) == WS_ERR_HIP);
     CHECK(ws_synapse_select_failed(fake, NULL, NULL) == WS_ERR_INVALID_ARG);
 
     CHECK(ws_synapse_gather(fake, fake, WS_BF16, H, 1000, 64, fake, 20, fake, fake, NULL) == WS_OK);

@@ -18,10 +18,14 @@ size_t select_workspace_bytes(int H, int L, int, bool) { return kSelectFlagBytes
 bool choose_select(int which, bool bf16, int, int L, int, const Chip &, size_t, SelectChoice &c)
 {
     c.resident = bf16 && which != 1 && L <= 65536;
+    if (!c.resident && L > 1000000) return false;      // as if not even one head's slabs fitted a budget
     c.stream = SelectPlan{8, 4, 512};
     c.res = ResidentShape{2, 0, 8, 16, 1};
     return !(which == 2 && !c.resident);
 }
+size_t stream_select_workspace_bytes(const SelectPlan &p, int L) { return kSelectFlagBytes + (size_t)p.groups * L * 8; }
+size_t resident_select_workspace_bytes(int H) { return kSelectFlagBytes + (size_t)H * 1024; }
+hipError_t select_static_scratch(void **) { return hipErrorNoDevice; }
 hipError_t launch_select(const SelectChoice &, const void *, bool, int, int, int, const float *, int, float, int32_t *,
                          float *, void *, hipStream_t)
 {

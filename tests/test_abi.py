@@ -41,8 +41,8 @@ def test_binding_has_the_same_names():
 
 def test_status_strings(lib):
     from paper_2601_01298_amd import binding
-    seen = {binding.status_string(s) for s in range(5)}
-    assert len(seen) == 5 and "ok" in seen
+    seen = {binding.status_string(s) for s in range(6)}
+    assert len(seen) == 6 and "ok" in seen
 
 
 def test_workspace_query(lib):
@@ -92,8 +92,14 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
         == b.WS_ERR_UNSUPPORTED                                               # fp32 keys have no on-chip kernel
     assert W(b.WS_SELECT_RESIDENT, fake, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, fake, None, fake, 8, None) == b.WS_ERR_WORKSPACE
     out = ctypes.c_int(7)
-    assert lib.ws_synapse_select_failed(None, None, ctypes.byref(out)) == b.WS_ERR_INVALID_ARG
     assert lib.ws_synapse_select_failed(fake, None, None) == b.WS_ERR_INVALID_ARG
+    T = lib.ws_synapse_select_static
+    assert T(fake, b.WS_BF16, 2, 100, 64, fake, 101, 0.5, fake, None, None) == b.WS_ERR_INVALID_ARG
+    assert T(fake, b.WS_BF16, 2, 100, 96, fake, 10, 0.5, fake, None, None) == b.WS_ERR_UNSUPPORTED
+    assert T(None, b.WS_BF16, 2, 100, 64, fake, 10, 0.5, fake, None, None) == b.WS_ERR_INVALID_ARG
+    # one head of the streaming kernel needs 8 bytes per key of slabs: more than the fixed 4 MiB
+    assert T(fake, b.WS_F32, 2, 600_000, 64, fake, 10, 0.5, fake, None, None) == b.WS_ERR_TOO_LARGE
+    assert T(fake, b.WS_BF16, 2, 1_000_000, 128, fake, 10, 0.5, fake, None, None) == b.WS_ERR_TOO_LARGE
     plan = b.SelectPlan()
     P = lib.ws_synapse_select_plan
     assert P(0, b.WS_BF16, 2, 100, 64, 0, 0, None) == b.WS_ERR_INVALID_ARG
