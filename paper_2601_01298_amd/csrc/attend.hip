@@ -27,6 +27,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 namespace {
 
@@ -41,19 +42,52 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float f)
 // (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
 __device__ __forceinline__ int mfma_row(int r, int hb) { return 8 * (r >> 2) + 4 * hb + (r & 3); }
 
+// LDS-only barrier: waits for this wave's LDS traffic, not for its global loads
+__device__ __forceinline__ void lds_only_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): lane i of the wave reads
+// base + byte_offset and lands at lds_base + 16 * i.  Completion is counted by vmcnt like any vector load;
+// the compiler does not see it, so the caller waits explicitly before the barrier that publishes the data.
+__device__ __forceinline__ void dma16(const void *base /* wave-uniform */, unsigned byte_offset, const void *lds_base)
+{
+    const unsigned la =
+        __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const void *)lds_base);
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_offset), "s"(base), "s"(la) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // One workgroup = 4 waves = 2 query tiles of one KV head x 2 halves of the landmark range; the
 // workgroups of a head are placed on the same accelerator die so its K_S/V_S rows are read from HBM
 // once and from that die's L2 otherwise.  The two halves run the online softmax independently and
 // are merged through LDS at the end: that gives every SIMD the same number of equally long waves
 // (at 100 agents a head has 4 query tiles; without the split some SIMDs would carry two of them
-// and some one).  The kernel is bound by vector-ALU issue (softmax and operand shuffling), not by
-// the MFMAs or by memory, so the per-tile instruction count is what is optimised:
+// and some one).
+//
+// Landmark rows reach the waves through LDS.  A stage is one 32-landmark tile of each half (K and V
+// rows: 4 tiles); the workgroup's 256 threads copy it global -> LDS asynchronously, 16 bytes per lane
+// with no registers in between, PF stages ahead into NBUF rotating buffers, and the two query-tile
+// waves of a half read the same copy.  So a workgroup fetches every landmark row once (not once per
+// query tile), a wave has PF stages of memory latency covered at no cost in registers, and the
+// operands arrive by LDS reads with constant offsets.  K tiles are stored with their 16-byte pieces
+// XOR-swizzled by row (applied on the global side of the copy) so that the MFMA operand reads, one
+// row per lane, spread over the banks; V tiles are stored as they are (their reads run along a row).
+// One LDS-only barrier per stage publishes the stage and retires the buffer that is refilled next.
+//
+// The per-tile instruction count is what is optimised in the softmax:
 //   - the score scale is folded into the exponent's FMA, the tile maximum is taken on raw scores;
 //   - the running maximum is only moved when a tile exceeds it by more than 2^8, so the
 //     accumulator is rescaled a few times per query instead of once per tile (weights stay below
 //     2^8, harmless in fp32 and in the bf16 hi+lo split);
-//   - packed conversions (v_cvt_pk_bf16_f32) and byte permutes (v_perm_b32) build the MFMA operands;
-//   - K and V operands of the next landmark tile are requested one tile ahead.
+//   - packed conversions (v_cvt_pk_bf16_f32) and byte permutes (v_perm_b32) build the MFMA operands.
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
 attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, const uint16_t *__restrict__ Vs,
@@ -61,6 +95,16 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 {
     constexpr int NK = D / 16;   // k-steps of the score product
     constexpr int NP = D / 64;   // 64-wide spans of head dimensions, each an even and an odd tile
+    constexpr int CH = D / 8;    // 16-byte pieces per landmark row
+    constexpr int TP = 32 * CH;  // pieces per 32-row tile
+    constexpr int NLD = TP / 256;              // copies per thread and tile
+    constexpr int NBUF = D == 64 ? 3 : 2;      // stage buffers (a stage: K and V tile of both halves)
+    constexpr int PF = NBUF - 1;               // stages in flight ahead of the one being read
+    constexpr int NC = 4 * NLD;                // copies per thread and stage
+    constexpr int NO = 2 * NP * 16;
+    constexpr int STG = 4 * TP;                // pieces per stage: [half][K tile, V tile]
+    constexpr int XCH = 2 * (NO + 2) * 64 * 4 / 16;                  // the merge area, in 16-byte units
+    __shared__ uint4 smem[NBUF * STG > XCH ? NBUF * STG : XCH];
     // workgroup id -> (head, part): parts of one head sit on one die (ids are dealt to the 8 dies round-robin)
     int h, part;
     if ((Hkv & 7) == 0) {
@@ -73,11 +117,11 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     }
     const int g = Hq / Hkv;
     const int M = N * g;         // query rows that read this KV head
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nq = lane & 31, hb = lane >> 5;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // the same for every lane: what follows from it is scalar
+    const int lane = tid & 63, nq = lane & 31, hb = lane >> 5;
     const uint16_t *Kh = Ks + (size_t)h * k * D;
     const uint16_t *Vh = Vs + (size_t)h * k * D;
-    constexpr int NO = 2 * NP * 16;
-    __shared__ float xch[2][NO + 2][64];
     const int wt = wave & 1, half = wave >> 1;
     const int tile = part * 2 + wt;
     const bool tile_live = tile * 32 < M;    // wave-uniform
@@ -85,11 +129,6 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     const bool valid = m < M;
     const int mc = valid ? m : M - 1;
     const int agent = mc / g, qh = h * g + mc % g;
-
-    const uint16_t *qrow = Q + ((size_t)agent * Hq + qh) * D;
-    bf16x8_t qf[NK];
-#pragma unroll
-    for (int kk = 0; kk < NK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8_t *>(qrow + kk * 16 + hb * 8);
 
     f32x16_t oacc[2 * NP];
 #pragma unroll
@@ -100,58 +139,87 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     float lrun = 0.0f;
 
     const int nT = (k + 31) / 32;
-    const int tA = (nT + 1) / 2;
-    const int tb = tile_live ? (half ? tA : 0) : 0;
-    const int te = tile_live ? (half ? nT : tA) : 0;
-    // Operands of the NEXT landmark tile, requested one tile ahead.  K: one 16-byte piece per k-step.
-    // V: the 32-bit word holding head dimensions (2 nq, 2 nq + 1) of 16 landmark rows; contraction slot
-    // (kk2, hb, e) <-> landmark t0 + mfma_row(8*kk2+e, hb) = t0 + 16 kk2 + 8 (e/4) + 4 hb + e%4.
-    bf16x8_t kn[NK];
-    uint32_t vn[2][NP][8];
-    auto fetch = [&](int t) {
-        const int t0 = t * 32;
-        if (t0 + 32 <= k) {      // full tile: one base address per lane, constant offsets
-            const uint16_t *krow = Kh + (size_t)(t0 + nq) * D + hb * 8;
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) kn[kk] = *reinterpret_cast<const bf16x8_t *>(krow + kk * 16);
-            const uint16_t *vbase = Vh + (size_t)(t0 + 4 * hb) * D + 2 * nq;
-#pragma unroll
-            for (int kk2 = 0; kk2 < 2; ++kk2)
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-#pragma unroll
-                    for (int p = 0; p < NP; ++p)
-                        vn[kk2][p][e] = *reinterpret_cast<const uint32_t *>(
-                            vbase + (16 * kk2 + 8 * (e >> 2) + (e & 3)) * D + 64 * p);
-        } else {                 // ragged last tile: clamp rows into the head (their weights are zero)
-            const uint16_t *krow = Kh + (size_t)min(t0 + nq, k - 1) * D + hb * 8;
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) kn[kk] = *reinterpret_cast<const bf16x8_t *>(krow + kk * 16);
-#pragma unroll
-            for (int kk2 = 0; kk2 < 2; ++kk2)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint16_t *vrow = Vh + (size_t)min(t0 + mfma_row(8 * kk2 + e, hb), k - 1) * D + 2 * nq;
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) vn[kk2][p][e] = *reinterpret_cast<const uint32_t *>(vrow + 64 * p);
-                }
-        }
-    };
-    if (tb < te) fetch(tb);
+    const int tA = (nT + 1) / 2;      // half 0 walks tiles [0, tA), half 1 [tA, nT): tA stages, the last may lack half 1
 
-    for (int t = tb; t < te; ++t) {
-        const int t0 = t * 32;
-        bf16x8_t kf[NK];
-        uint32_t vd[2][NP][8];
+    // ---- the copy: thread `tid` moves piece q = tid + 256 i of a tile, i.e. row q / CH, LDS slot q % CH; the K tile's
+    // slot c of row r holds piece c ^ (r & 7) (256 / CH rows further on the swizzle is the same: a multiple of 8).
+    // Byte offsets inside a head are 32-bit (k < 2^24 rows of at most 256 bytes); a row past the end clamps to the last.
+    constexpr unsigned RB = D * 2;                                   // bytes per landmark row
+    const int crow = tid / CH;
+    const unsigned kpiece = (unsigned)(((tid % CH) ^ (crow & 7)) * 16);
+    const unsigned vpiece = (unsigned)((tid % CH) * 16);
+    const unsigned last = (unsigned)(k - 1) * RB;
+    unsigned off0 = (unsigned)crow * RB;                             // this thread's first row of the next stage, half 0 ...
+    unsigned off1 = (unsigned)(tA * 32 + crow) * RB;                 // ... and half 1 (may lie past the end: clamped, never read)
+    auto issue = [&](int bi) {                                       // bi: stage buffer, a compile-time constant at every call
+        uint4 *buf = smem + bi * STG + wave * 64;
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) kf[kk] = kn[kk];
+        for (int i = 0; i < NLD; ++i) {
+            const unsigned r0 = min(off0 + (unsigned)(i * (256 / CH)) * RB, last);
+            const unsigned r1 = min(off1 + (unsigned)(i * (256 / CH)) * RB, last);
+            dma16(Kh, r0 + kpiece, buf + 0 * TP + 256 * i);
+            dma16(Vh, r0 + vpiece, buf + 1 * TP + 256 * i);
+            dma16(Kh, r1 + kpiece, buf + 2 * TP + 256 * i);
+            dma16(Vh, r1 + vpiece, buf + 3 * TP + 256 * i);
+        }
+        off0 += 32 * RB;
+        off1 += 32 * RB;
+    };
+
+    // The query rows are asked for first and the first stages' copies right behind them: every workgroup starts at the
+    // same moment, so what is asked for first arrives first, and the first tile needs the queries and stage 0 only.
+    // The query loads are written as assembly so that the compiler keeps no count for them (its wait at their first use,
+    // inside the loop, would also cover whatever copies are in flight by then); the wait below lets exactly the copies
+    // stay in flight, and the empty statement behind it pins the operands' first use after that wait.
+    const uint16_t *qrow = Q + ((size_t)agent * Hq + qh) * D + hb * 8;
+    u32x4_t qw[NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk)
+        asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qw[kk]) : "v"(qrow), "n"(kk * 32) : "memory");
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (p < tA) issue(p);
+    if (tA >= PF) wait_vmcnt<PF * NC>();
+    else wait_vmcnt<0>();
+    bf16x8_t qf[NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+        asm volatile("" : "+v"(qw[kk]));
+        qf[kk] = __builtin_bit_cast(bf16x8_t, qw[kk]);
+    }
+
+    // LDS read positions of this lane: K row nq of the tile (its swizzled pieces), V words of head dimensions 2nq, 2nq+1
+    int kslot[NK];
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) kslot[kk] = nq * CH + ((2 * kk + hb) ^ (nq & 7));
+
+    // One stage: `bi` is its buffer (a constant at every call, so LDS offsets are immediates)
+    auto stage = [&](int sidx, int bi) {
+        // this wave's copies of the stage have landed (those of later stages may still be in flight) ...
+        if (PF == 2 && sidx + 1 < tA) wait_vmcnt<NC>();
+        else wait_vmcnt<0>();
+        // ... and so have everybody's; all waves are through with the buffer that is refilled next
+        lds_only_barrier();
+        if (sidx + PF < tA) issue((bi + PF) % NBUF);
+        const int t = half ? tA + sidx : sidx;
+        if (!tile_live || t >= nT) return;             // wave-uniform
+        const int t0 = t * 32;
+        const uint4 *sK = smem + bi * STG + (half * 2 + 0) * TP;
+        const uint32_t *sV = reinterpret_cast<const uint32_t *>(smem + bi * STG + (half * 2 + 1) * TP);
+
+        bf16x8_t kf[NK];
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) kf[kk] = __builtin_bit_cast(bf16x8_t, sK[kslot[kk]]);
+        // V: the 32-bit word holding head dimensions (2 nq, 2 nq + 1) of 16 landmark rows; contraction slot
+        // (kk2, hb, e) <-> landmark t0 + mfma_row(8*kk2+e, hb) = t0 + 16 kk2 + 8 (e/4) + 4 hb + e%4.
+        uint32_t vd[2][NP][8];
 #pragma unroll
         for (int kk2 = 0; kk2 < 2; ++kk2)
 #pragma unroll
-            for (int p = 0; p < NP; ++p)
+            for (int e = 0; e < 8; ++e)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) vd[kk2][p][e] = vn[kk2][p][e];
-        if (t + 1 < te) fetch(t + 1);
+                for (int p = 0; p < NP; ++p)
+                    vd[kk2][p][e] = sV[(16 * kk2 + 8 * (e >> 2) + 4 * hb + (e & 3)) * (D / 2) + 32 * p + nq];
 
         // ---- S^T tile: rows = landmarks t0..t0+31, columns = queries
         f32x16_t sacc;
@@ -160,6 +228,7 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc, 0, 0, 0);
         if (t0 + 32 > k) {       // ragged last tile: landmarks past k get zero weight
+            asm volatile("" ::: "memory");              // (keeps this a branch: as selects it would run on every tile)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (t0 + mfma_row(r, hb) >= k) sacc[r] = -__builtin_inff();
@@ -226,9 +295,17 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
                 oacc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vo, pfl, oacc[2 * p + 1], 0, 0, 0);
             }
         }
+    };
+    for (int s0 = 0; s0 < tA; s0 += NBUF) {
+#pragma unroll
+        for (int bi = 0; bi < NBUF; ++bi)
+            if (s0 + bi < tA) stage(s0 + bi, bi);
     }
 
     // ---- merge the two halves of the landmark range: half 1 hands its state to half 0 through LDS
+    // (the merge area lies over the stage buffers: every wave is through with them first)
+    __syncthreads();
+    float(*xch)[NO + 2][64] = reinterpret_cast<float(*)[NO + 2][64]>(smem);
     if (half == 1) {
         xch[wt][NO][lane] = mref;
         xch[wt][NO + 1][lane] = lrun;
