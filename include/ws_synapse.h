@@ -19,7 +19,8 @@
  *   - The caller owns every buffer, including the workspace (size from
  *     ws_synapse_workspace_bytes, 256-byte aligned).  The library allocates nothing,
  *     keeps no state between calls, reads no environment variable and never synchronises
- *     the host (ws_synapse_select_failed, which reads a flag back, is the one exception):
+ *     the host (ws_synapse_select_failed and ws_synapse_density_check, which read a flag back, are
+ *     the exceptions):
  *     all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null
  *     stream), so a caller can run the producer on one stream and the agents on others
  *     (Sec. 3.1).  Two calls that share a workspace must be ordered by the caller.
@@ -69,10 +70,32 @@ typedef void *ws_stream; /* hipStream_t */
  *   K          dev  [H,L,d] keys, dtype `dt`
  *   sigma_host host [H] bandwidths, each finite and > 0 (read before the call returns)
  *   rho        dev  [H,L] fp32, written
+ *
+ * Accuracy.  The squared distances come from a Gram product on the matrix cores, so one kernel term
+ * carries a relative error of about 2^-23 * mean|k - c|^2 / sigma^2, where c is a reference point the
+ * library subtracts first: per head and coordinate the mid-range of the keys, wherever the differences
+ * k - c are exact in the keys' own format (a cloud sitting at a common offset, as real key caches do,
+ * is moved back to the origin at no loss; bf16 keys only).  The errors of different terms are independent
+ * and average down in the sum; with the bandwidth comparable to the cloud's spread (sigma^2 = tr(Cov)/16:
+ * estimate 2e-6) rho is within 5e-5 (bf16) / 1e-5 (fp32) of the exact value.  The estimate grows as the
+ * bandwidth shrinks below the spread and for offsets that cannot be removed exactly; every call writes it
+ * per head to the workspace and raises a flag when it exceeds 2e-5 (ws_synapse_density_check).  An isolated
+ * key's self term is exact whatever the estimate.  fp32 keys are swept in place (no translation).
  */
 ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d,
                              const float *sigma_host, float *rho,
                              void *workspace, size_t workspace_bytes, ws_stream stream);
+
+/* Accuracy report of the last ws_synapse_density enqueued on `stream` with this workspace (the first 256
+ * bytes of the workspace are the flag block, int32 flag at offset 0; H floats of estimates follow).  Waits
+ * for the stream (like ws_synapse_select_failed, this call synchronises the host), then writes to *flagged
+ * 1 if some head's estimated relative error per kernel term exceeds 2e-5, else 0, and, if err_est is not
+ * NULL, the H estimates (host array). */
+ws_status ws_synapse_density_check(const void *workspace, int H, ws_stream stream, int *flagged, float *err_est);
+
+/* Which sweep ws_synapse_density runs for these sizes: 1 = the symmetric sweep (every unordered pair once),
+ * 0 = the full sweep.  For reports and profiles. */
+int ws_synapse_density_is_symmetric(ws_dtype dt, int L, int d);
 
 /*
  * Greedy landmark choice per head (Sec. 3.3: coverage in the Hausdorff sense balanced
@@ -147,8 +170,8 @@ ws_status ws_synapse_select_static(const void *K, ws_dtype dt, int H, int L, int
 
 /* Did the last selection enqueued on `stream` with this workspace give up (see the co-residency
  * contract above)?  Waits for the stream, then writes 0 or 1 to *failed (host).  workspace == NULL
- * means the fixed scratch of ws_synapse_select_static on the current device.  This is the one call of
- * the library that synchronises the host. */
+ * means the fixed scratch of ws_synapse_select_static on the current device.  This call synchronises
+ * the host. */
 ws_status ws_synapse_select_failed(const void *workspace, ws_stream stream, int *failed);
 
 /* How a selection of these sizes is launched: which kernel, how many heads are in flight at once,

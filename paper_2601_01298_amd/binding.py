@@ -52,6 +52,10 @@ def lib() -> ctypes.CDLL:
         L.ws_synapse_density.restype = ci
         L.ws_synapse_select.argtypes = [vp, ci, ci, ci, ci, vp, ci, cf, vp, vp, vp, sz, vp]
         L.ws_synapse_select.restype = ci
+        L.ws_synapse_density_check.argtypes = [vp, ci, vp, ctypes.POINTER(ci), ctypes.POINTER(cf)]
+        L.ws_synapse_density_check.restype = ci
+        L.ws_synapse_density_is_symmetric.argtypes = [ci, ci, ci]
+        L.ws_synapse_density_is_symmetric.restype = ci
         L.ws_synapse_select_with.argtypes = [ci, vp, ci, ci, ci, ci, vp, ci, cf, vp, vp, vp, sz, vp]
         L.ws_synapse_select_with.restype = ci
         L.ws_synapse_select_static.argtypes = [vp, ci, ci, ci, ci, vp, ci, cf, vp, vp, vp]
@@ -169,6 +173,20 @@ def ws_synapse_density(K: torch.Tensor, sigma, rho: torch.Tensor | None = None, 
     _check(lib().ws_synapse_density(K.data_ptr(), dt, H, L, d, sig, rho.data_ptr(),
                                     workspace.data_ptr(), workspace.numel(), _stream(stream)), "ws_synapse_density")
     return rho
+
+
+def ws_synapse_density_check(workspace: torch.Tensor, H: int, stream=None):
+    """Waits for the stream; returns (flagged, estimates): whether some head's estimated relative error per kernel
+    term exceeded the library's bound in the last density call on this workspace, and the H estimates."""
+    flag = ctypes.c_int(0)
+    est = (ctypes.c_float * H)()
+    _check(lib().ws_synapse_density_check(_dev(workspace, "workspace").data_ptr(), int(H), _stream(stream),
+                                          ctypes.byref(flag), est), "ws_synapse_density_check")
+    return bool(flag.value), list(est)
+
+
+def ws_synapse_density_is_symmetric(dt: int, L: int, d: int) -> bool:
+    return bool(lib().ws_synapse_density_is_symmetric(dt, L, d))
 
 
 def ws_synapse_select(K: torch.Tensor, rho: torch.Tensor, k: int, alpha: float, idx: torch.Tensor | None = None,

@@ -78,6 +78,20 @@ ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d, co
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
 
+ws_status ws_synapse_density_check(const void *workspace, int H, ws_stream stream, int *flagged, float *err_est)
+{
+    if (!workspace || H < 1 || !flagged) return WS_ERR_INVALID_ARG;
+    int flag = 0;
+    const char *base = reinterpret_cast<const char *>(workspace);
+    if (hipMemcpyAsync(&flag, base, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess) return WS_ERR_HIP;
+    if (err_est && hipMemcpyAsync(err_est, base + ws::density_estimate_offset(), (size_t)H * sizeof(float),
+                                  hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
+        return WS_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return WS_ERR_HIP;
+    *flagged = flag != 0;
+    return WS_OK;
+}
+
 namespace {
 
 ws_status check_select_args(const void *K, ws_dtype dt, int H, int L, int d, const float *rho, int k, float alpha,
@@ -272,6 +286,12 @@ ws_status ws_synapse_inject(void *Kc, void *Vc, ws_dtype dt, int H, int Lcap, in
     const hipError_t e = ws::launch_inject(Kc, Vc, dt == WS_BF16, H, Lcap, d, L, Knew, Vnew, m, pos, base, workspace,
                                            (hipStream_t)stream);
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
+int ws_synapse_density_is_symmetric(ws_dtype dt, int L, int d)
+{
+    if (check_common(dt, d) != WS_OK || L < 1) return 0;
+    return ws::density_uses_symmetric(dt == WS_BF16, L, d) ? 1 : 0;
 }
 
 int ws_synapse_select_is_resident(ws_dtype dt, int H, int L, int d)

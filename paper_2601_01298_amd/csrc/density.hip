@@ -11,10 +11,23 @@
 // log2(e)/sigma^2, one v_exp_f32 and one add into a per-lane row accumulator: the sweep is
 // bound by the vector/transcendental pipe, not by the matrix pipe, so every instruction
 // removed there counts.  Padded key slots (index >= L) carry -1e30 in their record, which
-// drives their kernel value to exactly 0.  The exponent is formed from fp32 accumulators of
-// magnitude ~|k|^2, so a kernel term carries a relative error of about eps_fp32 * |k|^2 / sigma^2:
-// fine for bandwidths comparable to the spread of the cloud, meaningless for sigma -> 0 (where
-// only the exactly-handled self term survives anyway).
+// drives their kernel value to exactly 0.
+//
+// Accuracy and translation.  The exponent is formed from fp32 accumulators of magnitude ~|k|^2, so
+// a kernel term carries a relative error of about 2^-23 |k|^2 / sigma^2.  The density itself does
+// not depend on where the cloud sits, but that error does: a cloud with a common offset (what a
+// real key cache looks like) would lose accuracy in proportion to the offset squared.  So the
+// prepass moves the cloud: per head and coordinate it takes the mid-range c of the keys (rounded to
+// bf16) and, WHERE k - c IS EXACTLY A bf16 NUMBER FOR EVERY KEY of that coordinate (decided from the
+// coordinate's minimum, maximum and smallest non-zero magnitude: the keys of a coordinate with an
+// offset well above its spread all share a coarse grid, so their differences to c need few bits),
+// the sweep runs on a copy of the head holding k - c.  That copy is the same cloud, translated: no
+// rounding takes part.  Coordinates where the differences are not exact (a spread comparable to the
+// offset: little to gain there) keep c = 0; heads with c = 0 throughout are swept in place.  What is
+// left is reported: per head the estimate 2^-23 mean|k - c|^2 / sigma^2 is written to the head of the
+// workspace, and a flag is raised when it exceeds kErrBound (bandwidths far below the cloud's spread,
+// offsets that cannot be removed exactly).  For sigma -> 0 only the self term survives, and that one
+// is exact by construction.
 //
 // Work split: one workgroup (4 waves) owns RT*32 rows whose MFMA A-fragments stay in
 // registers for the whole sweep; the 4 waves stride over the 32-column tiles of the head and
@@ -93,40 +106,165 @@ __device__ __forceinline__ uint32_t bf16_rne(float f)
 }
 
 // ------------------------------------------------------------------------------------------
-// Prepass: per key, the squared norm in fp64 and its side record; per head, the exponent scale.
+// Prepass.
+//   density_stats   (bf16)  per head, coordinate and chunk of rows: minimum, maximum, smallest non-zero magnitude
+//   density_decide          per head: the reference point c (zero where k - c would not be exact), which copy of the
+//                           head the sweep reads, the exponent scale; clears the flag
+//   density_prep            per key: k - c written to the copy (heads that move), |k - c|^2 in fp64 and its side
+//                           record; per block of 256 keys the sum of the squared norms
+//   density_estimate        per head: 2^-23 mean|k - c|^2 / sigma^2, and the flag
 // ------------------------------------------------------------------------------------------
 struct ScaleChunk {
     float s[256];
 };
 
+constexpr int kStatChunks = 16;          // row chunks per head in density_stats
+constexpr float kErrBound = 2.0e-5f;     // estimated relative error of a kernel term above which a head is flagged
+
+struct PrepWs {
+    int *flag;              // [0] = 1 if some head's estimate exceeds kErrBound
+    float *est;             // [H] estimated relative error of one kernel term
+    float *scale;           // [H] log2(e) / sigma^2
+    const void **kbase;     // [H] the rows the sweep reads: the caller's, or the translated copy
+    float *cvec;            // [H][D] reference point
+    float *stat;            // [H][kStatChunks][3][D] min, max, smallest non-zero magnitude (bf16 keys only)
+    double *nsum;           // [H][Lpad/256] sum of squared norms per block of keys
+    uint4 *ext;             // [H][Lpad] side records
+    void *Kc;               // [H][L][D] translated copy (bf16 keys only)
+};
+
+template <int D>
+__global__ void __launch_bounds__(256)
+density_stats(const uint16_t *__restrict__ K, float *__restrict__ stat, int L)
+{
+    constexpr int CH = D / 8;            // 16-byte pieces per row
+    constexpr int RPS = 256 / CH;        // rows per sweep of the block
+    __shared__ float red[3][RPS][D + 1];
+    const int h = blockIdx.y, chunk = blockIdx.x;
+    const int per = (L + kStatChunks - 1) / kStatChunks;
+    const int lo = chunk * per, hi = min(L, lo + per);
+    const int piece = threadIdx.x % CH, r0 = threadIdx.x / CH;
+    float mn[8], mx[8], ma[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        mn[i] = __builtin_inff();
+        mx[i] = -__builtin_inff();
+        ma[i] = __builtin_inff();
+    }
+    const uint16_t *Kh = K + (size_t)h * L * D;
+    for (int r = lo + r0; r < hi; r += RPS) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(Kh + (size_t)r * D + piece * 8);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float v = __uint_as_float((i & 1) ? (w[i >> 1] & 0xFFFF0000u) : (w[i >> 1] << 16));
+            mn[i] = fminf(mn[i], v);
+            mx[i] = fmaxf(mx[i], v);
+            const float av = fabsf(v);
+            if (av > 0.0f) ma[i] = fminf(ma[i], av);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        red[0][r0][piece * 8 + i] = mn[i];
+        red[1][r0][piece * 8 + i] = mx[i];
+        red[2][r0][piece * 8 + i] = ma[i];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < 3 * D; c += 256) {
+        const int which = c / D, j = c % D;
+        float v = red[which][0][j];
+        for (int r = 1; r < RPS; ++r) v = (which == 1) ? fmaxf(v, red[which][r][j]) : fminf(v, red[which][r][j]);
+        stat[(((size_t)h * kStatChunks + chunk) * 3 + which) * D + j] = v;
+    }
+}
+
+// 2^(floor(log2 v) - 7): the spacing of bf16 numbers around |v| (v finite, normal, non-zero)
+__device__ __forceinline__ float bf16_ulp(float v)
+{
+    const uint32_t e = (__float_as_uint(v) >> 23) & 0xFFu;
+    return e > 7u ? __uint_as_float((e - 7u) << 23) : 0.0f;
+}
+
+template <int D>
+__global__ void __launch_bounds__(D)
+density_decide(PrepWs w, const void *K, size_t head_bytes, ScaleChunk sc, int head0, int centre)
+{
+    const int h = head0 + blockIdx.x, j = threadIdx.x;
+    float c = 0.0f;
+    if (centre) {
+        float mn = __builtin_inff(), mx = -__builtin_inff(), ma = __builtin_inff();
+        for (int ch = 0; ch < kStatChunks; ++ch) {
+            const float *st = w.stat + ((size_t)h * kStatChunks + ch) * 3 * D;
+            mn = fminf(mn, st[j]);
+            mx = fmaxf(mx, st[D + j]);
+            ma = fminf(ma, st[2 * D + j]);
+        }
+        if (mx >= mn && ma < __builtin_inff()) {          // finite, not all zero
+            const float mid = __uint_as_float(bf16_rne(0.5f * mn + 0.5f * mx) << 16);
+            if (mid != 0.0f && fabsf(mid) < __builtin_inff()) {
+                // every key of the coordinate and c are multiples of g (the finer of their bf16 spacings); k - c is a
+                // bf16 number when |k - c| <= 256 g.  g must be a normal number well inside the range.
+                const float g = fminf(bf16_ulp(ma), bf16_ulp(mid));
+                const float X = fmaxf(mx - mid, mid - mn) * 1.000001f;
+                if (g >= 7.0e-31f && X <= 256.0f * g) c = mid;
+            }
+        }
+    }
+    w.cvec[(size_t)h * D + j] = c;
+    const int moved = __syncthreads_or(c != 0.0f);
+    if (j == 0) {
+        w.kbase[h] = moved ? (const void *)((const char *)w.Kc + (size_t)h * head_bytes)
+                           : (const void *)((const char *)K + (size_t)h * head_bytes);
+        w.scale[h] = sc.s[blockIdx.x];
+        if (h == 0) w.flag[0] = 0;
+    }
+}
+
 template <class TR, int D>
 __global__ void __launch_bounds__(256)
-density_prep(const typename TR::Elem *__restrict__ K, uint4 *__restrict__ ext, float *__restrict__ scale,
-             ScaleChunk sc, int head0, int L, int Lpad)
+density_prep(const typename TR::Elem *__restrict__ K, PrepWs w, int L, int Lpad)
 {
-    const int h = head0 + blockIdx.y;
+    typedef typename TR::Elem Elem;
+    constexpr bool kBf16 = sizeof(Elem) == 2;
+    __shared__ double part[256];
+    const int h = blockIdx.y;
     const int j = blockIdx.x * 256 + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x == 0) scale[h] = sc.s[blockIdx.y];
-    if (j >= Lpad) return;
+    const float *cv = w.cvec + (size_t)h * D;
+    const bool moved = kBf16 && w.kbase[h] != (const void *)(K + (size_t)h * L * D);
     uint4 rec;
+    double n = 0.0;
     if (j < L) {
         // whole row through 16-byte loads (a thread owns a row: 8 or more loads hit the same lines)
         const uint4 *row = reinterpret_cast<const uint4 *>(K + ((size_t)h * L + j) * D);
-        constexpr int PER = 16 / sizeof(typename TR::Elem);
-        double n = 0.0;
+        uint4 *crow = reinterpret_cast<uint4 *>(reinterpret_cast<Elem *>(w.Kc) + ((size_t)h * L + j) * D);
+        constexpr int PER = 16 / sizeof(Elem);
 #pragma unroll 4
         for (int c = 0; c < D / PER; ++c) {
             const uint4 q = row[c];
-            typename TR::Elem e[PER];
+            Elem e[PER];
             __builtin_memcpy(e, &q, 16);
+            uint32_t xb[PER];
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
-                const double x = TR::widen(e[i]);
-                n += x * x;
+                if constexpr (kBf16) {
+                    // exact: c is non-zero only where every k - c of the coordinate is a bf16 number
+                    const float xf = __uint_as_float((uint32_t)e[i] << 16) - cv[c * PER + i];
+                    xb[i] = __float_as_uint(xf) >> 16;
+                    n += (double)xf * (double)xf;
+                } else {
+                    const double x = TR::widen(e[i]);
+                    n += x * x;
+                }
+            }
+            if constexpr (kBf16) {
+                if (moved)
+                    crow[c] = make_uint4(xb[0] | (xb[1] << 16), xb[2] | (xb[3] << 16), xb[4] | (xb[5] << 16),
+                                         xb[6] | (xb[7] << 16));
             }
         }
         double x = -0.5 * n;
-        if constexpr (sizeof(typename TR::Elem) == 2) {
+        if constexpr (kBf16) {
             uint32_t p[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -141,12 +279,33 @@ density_prep(const typename TR::Elem *__restrict__ K, uint4 *__restrict__ ext, f
         }
     } else {
         // padded slot: -1e30 makes exp2() of the pair exactly 0
-        if constexpr (sizeof(typename TR::Elem) == 2)
+        if constexpr (kBf16)
             rec = make_uint4(bf16_rne(-1e30f), 0u, 0x3F803F80u, 0x3F803F80u);
         else
             rec = make_uint4(__float_as_uint(-1e30f), 0u, 0u, 0u);
     }
-    ext[(size_t)h * Lpad + j] = rec;
+    if (j < Lpad) w.ext[(size_t)h * Lpad + j] = rec;
+    // sum of the block's squared norms, in a fixed order
+    part[threadIdx.x] = n;
+    __syncthreads();
+    for (int o = 128; o >= 1; o >>= 1) {
+        if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) w.nsum[(size_t)h * (Lpad / 256) + blockIdx.x] = part[0];
+}
+
+__global__ void __launch_bounds__(256)
+density_estimate(PrepWs w, int H, int L, int Lpad)
+{
+    const int h = blockIdx.x * 256 + threadIdx.x;
+    if (h >= H) return;
+    double t = 0.0;
+    for (int b = 0; b < Lpad / 256; ++b) t += w.nsum[(size_t)h * (Lpad / 256) + b];
+    // scale = log2(e) / sigma^2
+    const float est = (float)(1.1920928955078125e-7 * (t / (double)L) * ((double)w.scale[h] / 1.4426950408889634));
+    w.est[h] = est;
+    if (!(est <= kErrBound)) atomicExch(w.flag, 1);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -154,7 +313,7 @@ density_prep(const typename TR::Elem *__restrict__ K, uint4 *__restrict__ ext, f
 // ------------------------------------------------------------------------------------------
 template <class TR, int D, int RT>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-density_sweep(const typename TR::Elem *__restrict__ K, const uint4 *__restrict__ ext,
+density_sweep(const void *const *__restrict__ kbase, const uint4 *__restrict__ ext,
               const float *__restrict__ scale, float *__restrict__ rho, int L, int Lpad, int nRB, int total)
 {
     typedef typename TR::Frag Frag;
@@ -167,7 +326,7 @@ density_sweep(const typename TR::Elem *__restrict__ K, const uint4 *__restrict__
     const int logical = xcd_contiguous(blockIdx.x, total);
     const int h = logical / nRB;
     const int rb = logical - h * nRB;
-    const Elem *Kh = K + (size_t)h * L * D;
+    const Elem *Kh = reinterpret_cast<const Elem *>(kbase[h]);     // the caller's rows or their translated copy
     const uint4 *exth = ext + (size_t)h * Lpad;
     const float s = scale[h];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -348,7 +507,7 @@ __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], c
 
 template <int D, int RTW>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((D == 64 && RTW <= 2) ? 3 : 2, (D == 64 && RTW <= 2) ? 3 : 2)))
-density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const float *__restrict__ scale,
+density_sym(const void *const *__restrict__ kbase, const uint4 *__restrict__ ext, const float *__restrict__ scale,
             float *__restrict__ rowsum, float *__restrict__ colpart, int L, int Lpad, int nB, int nBoth, int head0,
             int total)
 {
@@ -366,7 +525,7 @@ density_sym(const uint16_t *__restrict__ K, const uint4 *__restrict__ ext, const
     const int logical = xcd_contiguous(blockIdx.x, total);
     const int hl = logical / nB, I = logical - hl * nB;
     const int h = head0 + hl;
-    const uint16_t *Kh = K + (size_t)h * L * D;
+    const uint16_t *Kh = reinterpret_cast<const uint16_t *>(kbase[h]);     // the caller's rows or their translated copy
     const uint4 *exth = ext + (size_t)h * Lpad;
     const float s = scale[h];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -523,7 +682,7 @@ static inline bool use_sym(bool bf16, int L, int d) { return bf16 && (L + sym_bm
 
 // ------------------------------------------------------------------------------------------
 struct DensityWs {
-    size_t scale, ext, rowsum, colpart, total;
+    size_t est, scale, kbase, cvec, stat, nsum, ext, kc, rowsum, colpart, total;
     int Lpad, nB, nBoth, chunk;
 };
 
@@ -531,9 +690,24 @@ static DensityWs density_layout(int H, int L, int d, bool bf16)
 {
     DensityWs w;
     w.Lpad = density_lpad(L);
-    w.scale = 0;
-    w.ext = round_up((size_t)H * sizeof(float), 256);
-    w.rowsum = w.ext + (size_t)H * w.Lpad * sizeof(uint4);
+    size_t o = kDensityFlagBytes;                               // the flag block sits in front
+    w.est = o;
+    o += round_up((size_t)H * sizeof(float), 256);
+    w.scale = o;
+    o += round_up((size_t)H * sizeof(float), 256);
+    w.kbase = o;
+    o += round_up((size_t)H * sizeof(void *), 256);
+    w.cvec = o;
+    o += round_up((size_t)H * d * sizeof(float), 256);
+    w.stat = o;
+    if (bf16) o += round_up((size_t)H * kStatChunks * 3 * d * sizeof(float), 256);
+    w.nsum = o;
+    o += round_up((size_t)H * (w.Lpad / 256) * sizeof(double), 256);
+    w.ext = o;
+    o += (size_t)H * w.Lpad * sizeof(uint4);
+    w.kc = o;
+    if (bf16) o += round_up((size_t)H * L * d * 2, 256);
+    w.rowsum = o;
     w.total = w.rowsum;
     w.nB = w.nBoth = w.chunk = 0;
     w.colpart = w.rowsum;
@@ -552,14 +726,38 @@ static DensityWs density_layout(int H, int L, int d, bool bf16)
 }
 
 size_t density_workspace_bytes(int H, int L, int d, bool bf16) { return density_layout(H, L, d, bf16).total; }
+size_t density_estimate_offset() { return kDensityFlagBytes; }
+
+static PrepWs prep_pointers(const DensityWs &w, char *base)
+{
+    PrepWs p;
+    p.flag = reinterpret_cast<int *>(base);
+    p.est = reinterpret_cast<float *>(base + w.est);
+    p.scale = reinterpret_cast<float *>(base + w.scale);
+    p.kbase = reinterpret_cast<const void **>(base + w.kbase);
+    p.cvec = reinterpret_cast<float *>(base + w.cvec);
+    p.stat = reinterpret_cast<float *>(base + w.stat);
+    p.nsum = reinterpret_cast<double *>(base + w.nsum);
+    p.ext = reinterpret_cast<uint4 *>(base + w.ext);
+    p.Kc = base + w.kc;
+    return p;
+}
 
 template <class TR, int D>
 static void run_prep(const void *K, int H, int L, const float *sigma_host, const DensityWs &w, char *base,
                      hipStream_t st)
 {
     typedef typename TR::Elem Elem;
-    float *scale = reinterpret_cast<float *>(base + w.scale);
-    uint4 *ext = reinterpret_cast<uint4 *>(base + w.ext);
+    constexpr bool kBf16 = sizeof(Elem) == 2;
+    const PrepWs p = prep_pointers(w, base);
+    if constexpr (kBf16) {
+        for (int h0 = 0; h0 < H; h0 += 32768) {      // grid.y is 16 bits wide
+            const int nh = (H - h0 < 32768) ? H - h0 : 32768;
+            hipLaunchKernelGGL((density_stats<D>), dim3(kStatChunks, nh), dim3(256), 0, st,
+                               reinterpret_cast<const uint16_t *>(K) + (size_t)h0 * L * D,
+                               p.stat + (size_t)h0 * kStatChunks * 3 * D, L);
+        }
+    }
     for (int h0 = 0; h0 < H; h0 += 256) {
         const int nh = (H - h0 < 256) ? H - h0 : 256;
         ScaleChunk sc;
@@ -568,10 +766,21 @@ static void run_prep(const void *K, int H, int L, const float *sigma_host, const
             const double sg = (i < nh) ? (double)sigma_host[h0 + i] : 1.0;
             sc.s[i] = (float)(1.4426950408889634 / (sg * sg));
         }
-        dim3 grid((w.Lpad + 255) / 256, nh);
-        hipLaunchKernelGGL((density_prep<TR, D>), grid, dim3(256), 0, st, reinterpret_cast<const Elem *>(K), ext,
-                           scale, sc, h0, L, w.Lpad);
+        hipLaunchKernelGGL((density_decide<D>), dim3(nh), dim3(D), 0, st, p, K, (size_t)L * D * sizeof(Elem), sc, h0,
+                           kBf16 ? 1 : 0);
     }
+    for (int h0 = 0; h0 < H; h0 += 32768) {      // grid.y is 16 bits wide
+        const int nh = (H - h0 < 32768) ? H - h0 : 32768;
+        PrepWs q = p;
+        q.cvec += (size_t)h0 * D;
+        q.kbase += h0;
+        q.nsum += (size_t)h0 * (w.Lpad / 256);
+        q.ext += (size_t)h0 * w.Lpad;
+        q.Kc = reinterpret_cast<char *>(q.Kc) + (size_t)h0 * L * D * sizeof(Elem);
+        hipLaunchKernelGGL((density_prep<TR, D>), dim3(w.Lpad / 256, nh), dim3(256), 0, st,
+                           reinterpret_cast<const Elem *>(K) + (size_t)h0 * L * D, q, L, w.Lpad);
+    }
+    hipLaunchKernelGGL(density_estimate, dim3((H + 255) / 256), dim3(256), 0, st, p, H, L, w.Lpad);
 }
 
 template <class TR, int D, int RT>
@@ -586,7 +795,7 @@ static hipError_t run(const void *K, int H, int L, const float *sigma_host, floa
     const long long total = (long long)nRB * H;
     if (total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((density_sweep<TR, D, RT>), dim3((unsigned)total), dim3(256), 0, st,
-                       reinterpret_cast<const Elem *>(K), reinterpret_cast<const uint4 *>(base + w.ext),
+                       reinterpret_cast<const void *const *>(base + w.kbase), reinterpret_cast<const uint4 *>(base + w.ext),
                        reinterpret_cast<const float *>(base + w.scale), rho, L, w.Lpad, nRB, (int)total);
     return hipGetLastError();
 }
@@ -603,7 +812,7 @@ static hipError_t run_sym(const void *K, int H, int L, const float *sigma_host, 
         const int nh = (H - h0 < w.chunk) ? H - h0 : w.chunk;
         const int total = nh * w.nB;
         hipLaunchKernelGGL((density_sym<D, RTW>), dim3(total), dim3(256), 0, st,
-                           reinterpret_cast<const uint16_t *>(K), reinterpret_cast<const uint4 *>(base + w.ext),
+                           reinterpret_cast<const void *const *>(base + w.kbase), reinterpret_cast<const uint4 *>(base + w.ext),
                            reinterpret_cast<const float *>(base + w.scale), rowsum, colpart, L, w.Lpad, w.nB, w.nBoth,
                            h0, total);
         hipLaunchKernelGGL(density_finish, dim3((L + 255) / 256, nh), dim3(256), 0, st, rowsum, colpart, rho, L,
@@ -628,5 +837,8 @@ hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const f
     }
     return hipErrorInvalidValue;
 }
+
+// which sweep serves these sizes (for reports): 1 = symmetric, 0 = full
+bool density_uses_symmetric(bool bf16, int L, int d) { return use_sym(bf16, L, d); }
 
 }  // namespace ws

@@ -35,7 +35,10 @@ __device__ __forceinline__ float lane_group_sum(float v)
 // ---- density -------------------------------------------------------------------------
 // Keys per head are padded to a multiple of 512 in the per-key side records.
 static inline int density_lpad(int L) { return (int)round_up((size_t)L, 512); }
+constexpr size_t kDensityFlagBytes = 256;     // head of the density workspace: int32 accuracy flag at offset 0
 size_t density_workspace_bytes(int H, int L, int d, bool bf16);
+size_t density_estimate_offset();             // where the per-head error estimates start (H floats)
+bool density_uses_symmetric(bool bf16, int L, int d);
 // sigma_host[h] > 0 (validated by the caller); enqueues prepass + main sweep.
 hipError_t launch_density(const void *K, bool bf16, int H, int L, int d, const float *sigma_host,
                           float *rho, void *ws, hipStream_t st);

@@ -78,6 +78,80 @@ def test_density_fp32_d128_and_sigma_extremes(ws, oracle):
     assert np.abs(rho[0] / ref - 1).max() <= 1e-5 and rho[0, 10] == rho[0, 3]
 
 
+def density_with_report(ws, Kd, sigma):
+    import torch
+    H, L, d = Kd.shape
+    dt = ws.WS_BF16 if Kd.dtype == torch.bfloat16 else ws.WS_F32
+    wsb = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_DENSITY, dt, H, L, d), dtype=torch.uint8, device="cuda")
+    rho = ws.ws_synapse_density(Kd, sigma, workspace=wsb).cpu().numpy()
+    flagged, est = ws.ws_synapse_density_check(wsb, H)
+    return rho, flagged, np.array(est)
+
+
+@pytest.mark.parametrize("L", [2048, 600])            # the symmetric sweep and the full sweep
+@pytest.mark.parametrize("offset", [20.0, 100.0, -1000.0])
+def test_density_of_a_translated_cloud(ws, oracle, L, offset):
+    """The density does not depend on where the cloud sits (the oracle pins that), and real key caches sit at an
+    offset.  A cloud drawn around the origin is moved by a common offset BEFORE it is rounded to bf16, so the keys
+    handed to both sides are the rounded, translated ones.  The Gram form alone would lose |offset|^2 d / sigma^2
+    in accuracy (x 1e4 at offset 100); the library translates the head back exactly first."""
+    w = variant(2, H=3, L=L)
+    rng = np.random.default_rng(int(abs(offset)) + L)
+    K = np.empty((w.H, L, w.d), dtype=np.float32)
+    for h in range(w.H):
+        x = syn.cloud(w, h, syn.TENSOR_K).astype(np.float64)
+        shift = np.full(w.d, offset)
+        if h == 1:
+            shift = shift * rng.choice([0.0, 1.0, -0.5], size=w.d)        # some coordinates at the origin, some mirrored
+        if h == 2:
+            shift = offset * rng.uniform(0.5, 2.0, size=w.d)              # a different offset per coordinate
+        K[h] = syn.round_to_bf16((x + shift).astype(np.float32))
+    sigma = [syn.bandwidth(K[h]) for h in range(w.H)]
+    rho, flagged, est = density_with_report(ws, to_device(K, "bf16"), sigma)
+    for h in range(w.H):
+        ref = oracle.density(K[h], float(sigma[h]))
+        err = np.abs(rho[h] / ref - 1).max()
+        norm = (K[h].astype(np.float64) ** 2).sum(1).mean() / float(sigma[h]) ** 2
+        print(f"offset {offset} L={L} head {h}: max rel err {err:.2e}; estimate {est[h]:.1e} "
+              f"(uncentred it would be {2.0 ** -23 * norm:.1e})")
+        assert err <= RHO_TOL["bf16"]
+        assert est[h] <= 1e-5
+    assert not flagged
+
+
+def test_density_reports_what_it_cannot_guarantee(ws, oracle):
+    """Cases outside the accurate range must be visible to the caller, never silently wrong: (a) an offset that
+    cannot be removed exactly (one key of the offset coordinates lies near zero, so the differences to the
+    mid-range need more bits than bf16 has); (b) a bandwidth far below the cloud's spread (sigma^2 = tr(Cov)/256).
+    For each head: within tolerance, or flagged."""
+    w = variant(2, H=2, L=2048)
+    K = np.stack([syn.cloud(w, h, syn.TENSOR_K) for h in range(w.H)]).astype(np.float64)
+    K += 300.0
+    K[0, 17] = 0.001                                   # head 0: every coordinate has one key near zero
+    K = syn.round_to_bf16(K.astype(np.float32))
+    sigma = [syn.bandwidth(K[h]) for h in range(w.H)]
+    rho, flagged, est = density_with_report(ws, to_device(K, "bf16"), sigma)
+    errs = [float(np.abs(rho[h] / oracle.density(K[h], float(sigma[h])) - 1).max()) for h in range(w.H)]
+    print(f"unremovable offset: errors {errs[0]:.2e} / {errs[1]:.2e}, estimates {est[0]:.1e} / {est[1]:.1e}, flagged {flagged}")
+    assert flagged and est[0] > 2e-5                  # head 0 is reported ...
+    assert est[1] <= 1e-5 and errs[1] <= RHO_TOL["bf16"]      # ... head 1 (no such key) is moved and accurate
+    # (b) small bandwidth on a centred cloud
+    K = np.stack([syn.cloud(w, h, syn.TENSOR_K) for h in range(w.H)])
+    sigma = [float(syn.bandwidth(K[h])) / 4.0 for h in range(w.H)]
+    rho, flagged, est = density_with_report(ws, to_device(K, "bf16"), sigma)
+    for h in range(w.H):
+        err = float(np.abs(rho[h] / oracle.density(K[h], sigma[h]) - 1).max())
+        print(f"sigma^2 = tr(Cov)/256 head {h}: max rel err {err:.2e}, estimate {est[h]:.1e}, flagged {flagged}")
+        assert err <= RHO_TOL["bf16"] or (flagged and est[h] > 2e-5)
+    # fp32 keys are swept in place: an offset shows up in the estimate
+    Kf = (np.random.default_rng(3).standard_normal((1, 300, 64)) + 50.0).astype(np.float32)
+    sg = [float(syn.bandwidth(Kf[0]))]
+    rho, flagged, est = density_with_report(ws, to_device(Kf, "f32"), sg)
+    err = float(np.abs(rho[0] / oracle.density(Kf[0], sg[0]) - 1).max())
+    print(f"fp32 keys at offset 50: max rel err {err:.2e}, estimate {est[0]:.1e}, flagged {flagged}")
+    assert err <= RHO_TOL["f32"] or flagged
+
+
 # ------------------------------------------------------------------------------ selection
 @pytest.mark.parametrize("alpha", [0.0, 0.25, 0.5, 1.0])
 def test_select_tiny_config_all_alphas(ws, oracle, alpha, select_kernel):
