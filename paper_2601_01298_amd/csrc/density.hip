@@ -126,23 +126,32 @@ struct PrepWs {
     float *est;             // [H] estimated relative error of one kernel term
     float *scale;           // [H] log2(e) / sigma^2
     const void **kbase;     // [H] the rows the sweep reads: the caller's, or the translated copy
+    int *cand;              // [H] some coordinate of the head may be moved (after the sample pass); moved (after the full one)
     float *cvec;            // [H][D] reference point
     float *stat;            // [H][kStatChunks][3][D] min, max, smallest non-zero magnitude (bf16 keys only)
     double *nsum;           // [H][Lpad/256] sum of squared norms per block of keys
     uint4 *ext;             // [H][Lpad] side records
     void *Kc;               // [H][L][D] translated copy (bf16 keys only)
+    unsigned long long *acc;   // [H][Lpad] kernel sums in fixed point (symmetric sweep only, else NULL): cleared here
 };
 
+// Two passes.  Pass 0 looks at the first eighth of every chunk of rows.  More keys only widen a coordinate's range
+// and refine its grid, so a coordinate that fails the exactness test on the sample is taken to fail it on the whole
+// head (a rule on the safe side: it decides only whether a head is moved, never a value): heads without a candidate
+// coordinate are settled by the sample, and pass 1, which reads the rest and merges, skips them.
 template <int D>
 __global__ void __launch_bounds__(256)
-density_stats(const uint16_t *__restrict__ K, float *__restrict__ stat, int L)
+density_stats(const uint16_t *__restrict__ K, float *__restrict__ stat, int L, int pass, const int *__restrict__ cand)
 {
     constexpr int CH = D / 8;            // 16-byte pieces per row
     constexpr int RPS = 256 / CH;        // rows per sweep of the block
     __shared__ float red[3][RPS][D + 1];
     const int h = blockIdx.y, chunk = blockIdx.x;
+    if (pass == 1 && !cand[h]) return;
     const int per = (L + kStatChunks - 1) / kStatChunks;
-    const int lo = chunk * per, hi = min(L, lo + per);
+    const int cut = chunk * per + (per + 7) / 8;
+    const int lo = pass == 0 ? chunk * per : min(L, cut);
+    const int hi = pass == 0 ? min(L, cut) : min(L, (chunk + 1) * per);
     const int piece = threadIdx.x % CH, r0 = threadIdx.x / CH;
     float mn[8], mx[8], ma[8];
 #pragma unroll
@@ -175,7 +184,9 @@ density_stats(const uint16_t *__restrict__ K, float *__restrict__ stat, int L)
         const int which = c / D, j = c % D;
         float v = red[which][0][j];
         for (int r = 1; r < RPS; ++r) v = (which == 1) ? fmaxf(v, red[which][r][j]) : fminf(v, red[which][r][j]);
-        stat[(((size_t)h * kStatChunks + chunk) * 3 + which) * D + j] = v;
+        float *dst = stat + (((size_t)h * kStatChunks + chunk) * 3 + which) * D + j;
+        if (pass == 1) v = (which == 1) ? fmaxf(v, *dst) : fminf(v, *dst);
+        *dst = v;
     }
 }
 
@@ -216,6 +227,7 @@ density_decide(PrepWs w, const void *K, size_t head_bytes, ScaleChunk sc, int he
     if (j == 0) {
         w.kbase[h] = moved ? (const void *)((const char *)w.Kc + (size_t)h * head_bytes)
                            : (const void *)((const char *)K + (size_t)h * head_bytes);
+        w.cand[h] = moved;
         w.scale[h] = sc.s[blockIdx.x];
         if (h == 0) w.flag[0] = 0;
     }
@@ -239,28 +251,37 @@ density_prep(const typename TR::Elem *__restrict__ K, PrepWs w, int L, int Lpad)
         const uint4 *row = reinterpret_cast<const uint4 *>(K + ((size_t)h * L + j) * D);
         uint4 *crow = reinterpret_cast<uint4 *>(reinterpret_cast<Elem *>(w.Kc) + ((size_t)h * L + j) * D);
         constexpr int PER = 16 / sizeof(Elem);
-#pragma unroll 4
-        for (int c = 0; c < D / PER; ++c) {
-            const uint4 q = row[c];
-            Elem e[PER];
-            __builtin_memcpy(e, &q, 16);
-            uint32_t xb[PER];
+        constexpr int NPC = D / PER;             // 16-byte pieces per row
+        constexpr int GRP = NPC < 8 ? NPC : 8;   // pieces in flight at a time (all loads of a group before any store)
 #pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                if constexpr (kBf16) {
-                    // exact: c is non-zero only where every k - c of the coordinate is a bf16 number
-                    const float xf = __uint_as_float((uint32_t)e[i] << 16) - cv[c * PER + i];
-                    xb[i] = __float_as_uint(xf) >> 16;
-                    n += (double)xf * (double)xf;
-                } else {
-                    const double x = TR::widen(e[i]);
-                    n += x * x;
+        for (int c0 = 0; c0 < NPC; c0 += GRP) {
+            uint4 qs[GRP];
+#pragma unroll
+            for (int c = 0; c < GRP; ++c) qs[c] = row[c0 + c];
+#pragma unroll
+            for (int c = 0; c < GRP; ++c) {
+                Elem e[PER];
+                __builtin_memcpy(e, &qs[c], 16);
+                uint32_t xb[PER];
+#pragma unroll
+                for (int i = 0; i < PER; ++i) {
+                    if constexpr (kBf16) {
+                        // exact: c is non-zero only where every k - c of the coordinate is a bf16 number
+                        // (heads that stay in place skip the reference point: it is zero throughout)
+                        float xf = __uint_as_float((uint32_t)e[i] << 16);
+                        if (moved) xf -= cv[(c0 + c) * PER + i];
+                        xb[i] = __float_as_uint(xf) >> 16;
+                        n += (double)xf * (double)xf;
+                    } else {
+                        const double x = TR::widen(e[i]);
+                        n += x * x;
+                    }
                 }
-            }
-            if constexpr (kBf16) {
-                if (moved)
-                    crow[c] = make_uint4(xb[0] | (xb[1] << 16), xb[2] | (xb[3] << 16), xb[4] | (xb[5] << 16),
-                                         xb[6] | (xb[7] << 16));
+                if constexpr (kBf16) {
+                    if (moved)
+                        crow[c0 + c] = make_uint4(xb[0] | (xb[1] << 16), xb[2] | (xb[3] << 16), xb[4] | (xb[5] << 16),
+                                                  xb[6] | (xb[7] << 16));
+                }
             }
         }
         double x = -0.5 * n;
@@ -284,7 +305,10 @@ density_prep(const typename TR::Elem *__restrict__ K, PrepWs w, int L, int Lpad)
         else
             rec = make_uint4(__float_as_uint(-1e30f), 0u, 0u, 0u);
     }
-    if (j < Lpad) w.ext[(size_t)h * Lpad + j] = rec;
+    if (j < Lpad) {
+        w.ext[(size_t)h * Lpad + j] = rec;
+        if (w.acc) w.acc[(size_t)h * Lpad + j] = 0ull;
+    }
     // sum of the block's squared norms, in a fixed order
     part[threadIdx.x] = n;
     __syncthreads();
@@ -447,9 +471,10 @@ __device__ __forceinline__ void wait_vmcnt()
 // blocks I (row sums only), I+1 .. I+nBoth (row and column sums) and, when the block count is
 // even, I + nB/2 (row sums only; its partner evaluates the transposed copy).  Every workgroup
 // does the same amount of work.  Row sums stay in registers for the whole sweep.  Column sums
-// of one visited block are reduced over the workgroup's 4 waves in LDS and written to slot
-// (J - I - 1) of a partial-sum array; a last small kernel adds row sums and slots in a fixed
-// order, so the result does not depend on scheduling.
+// of one visited block are reduced over the workgroup's 4 waves in LDS and added to the keys'
+// accumulator cells (fixed point, integer atomics: see fixed_add), as are the row sums at the
+// end; a last small kernel turns the cells into rho.  Integer addition is associative, so the
+// result does not depend on scheduling.
 //
 // The 4 waves of a workgroup own different rows (RTW tiles of 32 each) and share the stream of
 // column tiles: 64 key rows per stage reach the LDS by asynchronous global -> LDS copies (no
@@ -458,6 +483,18 @@ __device__ __forceinline__ void wait_vmcnt()
 // 8 different bank groups; the swizzle is applied on the global side of the copy).  One LDS-only
 // barrier per stage publishes the stage and retires the buffer two stages back.
 // ------------------------------------------------------------------------------------------
+// The kernel sums of a key come from many workgroups (its own row block, and every block that visits it as
+// a column block).  They are accumulated in 32.32 fixed point with integer atomics: integer addition is
+// associative, so the result does not depend on the order in which the workgroups arrive (a floating-point
+// atomic would), and one 8-byte cell per key replaces a slot per visiting workgroup.  A contribution is a sum
+// of at most a few hundred kernel values (<= 1 each), the total at most L < 2^24: no overflow, and the 2^-32
+// resolution is far below fp32 rounding of sums that are >= 1 (the self term).
+__device__ __forceinline__ void fixed_add(unsigned long long *cell, float v)
+{
+    const unsigned long long q = (unsigned long long)__float2ll_rn(v * 4294967296.0f);
+    __hip_atomic_fetch_add(cell, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int D, int RTW, bool BOTH, bool DIAG>
 __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], const bf16x8_t (&b)[D / 16 + 1],
                                          float (&racc)[RTW][16], float &csum, float s, int n, int hb,
@@ -508,8 +545,7 @@ __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], c
 template <int D, int RTW>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((D == 64 && RTW <= 2) ? 3 : 2, (D == 64 && RTW <= 2) ? 3 : 2)))
 density_sym(const void *const *__restrict__ kbase, const uint4 *__restrict__ ext, const float *__restrict__ scale,
-            float *__restrict__ rowsum, float *__restrict__ colpart, int L, int Lpad, int nB, int nBoth, int head0,
-            int total)
+            unsigned long long *__restrict__ acc, int L, int Lpad, int nB, int nBoth, int head0, int total)
 {
     constexpr int NK = D / 16, NS = NK + 1;
     constexpr int BM = 4 * RTW * 32;       // rows (and columns) per block
@@ -623,12 +659,10 @@ density_sym(const void *const *__restrict__ kbase, const uint4 *__restrict__ ext
         if (both && sin == SPB - 1) {
             __syncthreads();
             const int J = (I + j) % nB;
-            float *dst = colpart + ((size_t)hl * nBoth + (j - 1)) * Lpad + (size_t)J * BM;
-            // written once, read once by the last kernel: non-temporal, so the partial sums do not push the key tiles out of the L2
+            unsigned long long *dst = acc + (size_t)h * Lpad + (size_t)J * BM;
             for (int c = tid; c < BM; c += 256)
-                __builtin_nontemporal_store(((cs[0][0][c] + cs[0][1][c]) + (cs[1][0][c] + cs[1][1][c])) +
-                                                ((cs[2][0][c] + cs[2][1][c]) + (cs[3][0][c] + cs[3][1][c])),
-                                            dst + c);
+                fixed_add(dst + c, ((cs[0][0][c] + cs[0][1][c]) + (cs[1][0][c] + cs[1][1][c])) +
+                                       ((cs[2][0][c] + cs[2][1][c]) + (cs[3][0][c] + cs[3][1][c])));
         }
     }
 
@@ -644,37 +678,23 @@ density_sym(const void *const *__restrict__ kbase, const uint4 *__restrict__ ext
             v += __shfl_xor(v, 8);
             v += __shfl_xor(v, 16);
             if (n == 0)
-                rowsum[(size_t)hl * Lpad + I * BM + (wave * RTW + rt) * 32 + 8 * (r >> 2) + 4 * hb + (r & 3)] = v;
+                fixed_add(acc + (size_t)h * Lpad + I * BM + (wave * RTW + rt) * 32 + 8 * (r >> 2) + 4 * hb + (r & 3), v);
         }
 }
 
-// rho = (row sum + column partial sums in slot order) / L
+// rho = accumulated kernel sum / L
 __global__ void __launch_bounds__(256)
-density_finish(const float *__restrict__ rowsum, const float *__restrict__ colpart, float *__restrict__ rho, int L,
-               int Lpad, int nBoth, int head0)
+density_finish(const unsigned long long *__restrict__ acc, float *__restrict__ rho, int L, int Lpad, int head0)
 {
-    const int hl = blockIdx.y;
+    const int h = head0 + blockIdx.y;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= L) return;
-    float t = rowsum[(size_t)hl * Lpad + i];
-    const float *cp = colpart + (size_t)hl * nBoth * Lpad + i;
-    // slot order is fixed; eight loads are in flight at a time
-    int sl = 0;
-    for (; sl + 8 <= nBoth; sl += 8) {
-        float v[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(cp + (size_t)(sl + j) * Lpad);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) t += v[j];
-    }
-    for (; sl < nBoth; ++sl) t += __builtin_nontemporal_load(cp + (size_t)sl * Lpad);
-    rho[(size_t)(head0 + hl) * L + i] = t / (float)L;
+    const double t = (double)acc[(size_t)h * Lpad + i] * (1.0 / 4294967296.0);
+    rho[(size_t)h * L + i] = (float)(t / (double)L);
 }
 
-// Heads go through the symmetric sweep in as few launches as the column partial sums allow: their
-// workspace (heads x slots x keys x 4 bytes) is kept under 4 GiB, and a launch takes at most 1024 heads.
-constexpr size_t kSymPartialBytes = (size_t)4 << 30;
-constexpr int kSymChunkHeads = 1024;
+// A launch of the symmetric sweep takes at most this many heads.
+constexpr int kSymChunkHeads = 16384;
 
 constexpr int kSymRtw64 = 2, kSymRtw128 = 2;   // row tiles per wave
 static inline int sym_bm(int d) { return 128 * (d == 64 ? kSymRtw64 : kSymRtw128); }
@@ -682,8 +702,8 @@ static inline bool use_sym(bool bf16, int L, int d) { return bf16 && (L + sym_bm
 
 // ------------------------------------------------------------------------------------------
 struct DensityWs {
-    size_t est, scale, kbase, cvec, stat, nsum, ext, kc, rowsum, colpart, total;
-    int Lpad, nB, nBoth, chunk;
+    size_t est, scale, kbase, cand, cvec, stat, nsum, ext, kc, acc, total;
+    int Lpad, nB, nBoth;
 };
 
 static DensityWs density_layout(int H, int L, int d, bool bf16)
@@ -697,6 +717,8 @@ static DensityWs density_layout(int H, int L, int d, bool bf16)
     o += round_up((size_t)H * sizeof(float), 256);
     w.kbase = o;
     o += round_up((size_t)H * sizeof(void *), 256);
+    w.cand = o;
+    o += round_up((size_t)H * sizeof(int), 256);
     w.cvec = o;
     o += round_up((size_t)H * d * sizeof(float), 256);
     w.stat = o;
@@ -707,21 +729,14 @@ static DensityWs density_layout(int H, int L, int d, bool bf16)
     o += (size_t)H * w.Lpad * sizeof(uint4);
     w.kc = o;
     if (bf16) o += round_up((size_t)H * L * d * 2, 256);
-    w.rowsum = o;
-    w.total = w.rowsum;
-    w.nB = w.nBoth = w.chunk = 0;
-    w.colpart = w.rowsum;
+    w.acc = o;
+    w.nB = w.nBoth = 0;
     if (use_sym(bf16, L, d)) {
         w.nB = w.Lpad / sym_bm(d);
         w.nBoth = (w.nB - 1) / 2;
-        const size_t per_head = (size_t)w.nBoth * w.Lpad * sizeof(float);
-        size_t fit = per_head ? kSymPartialBytes / per_head : (size_t)kSymChunkHeads;
-        if (fit < 1) fit = 1;
-        if (fit > (size_t)kSymChunkHeads) fit = kSymChunkHeads;
-        w.chunk = (size_t)H < fit ? H : (int)fit;
-        w.colpart = w.rowsum + round_up((size_t)w.chunk * w.Lpad * sizeof(float), 256);
-        w.total = w.colpart + round_up((size_t)w.chunk * w.nBoth * w.Lpad * sizeof(float), 256);
+        o += round_up((size_t)H * w.Lpad * sizeof(unsigned long long), 256);
     }
+    w.total = o;
     return w;
 }
 
@@ -735,11 +750,13 @@ static PrepWs prep_pointers(const DensityWs &w, char *base)
     p.est = reinterpret_cast<float *>(base + w.est);
     p.scale = reinterpret_cast<float *>(base + w.scale);
     p.kbase = reinterpret_cast<const void **>(base + w.kbase);
+    p.cand = reinterpret_cast<int *>(base + w.cand);
     p.cvec = reinterpret_cast<float *>(base + w.cvec);
     p.stat = reinterpret_cast<float *>(base + w.stat);
     p.nsum = reinterpret_cast<double *>(base + w.nsum);
     p.ext = reinterpret_cast<uint4 *>(base + w.ext);
     p.Kc = base + w.kc;
+    p.acc = w.nB ? reinterpret_cast<unsigned long long *>(base + w.acc) : nullptr;
     return p;
 }
 
@@ -750,24 +767,26 @@ static void run_prep(const void *K, int H, int L, const float *sigma_host, const
     typedef typename TR::Elem Elem;
     constexpr bool kBf16 = sizeof(Elem) == 2;
     const PrepWs p = prep_pointers(w, base);
-    if constexpr (kBf16) {
-        for (int h0 = 0; h0 < H; h0 += 32768) {      // grid.y is 16 bits wide
-            const int nh = (H - h0 < 32768) ? H - h0 : 32768;
-            hipLaunchKernelGGL((density_stats<D>), dim3(kStatChunks, nh), dim3(256), 0, st,
-                               reinterpret_cast<const uint16_t *>(K) + (size_t)h0 * L * D,
-                               p.stat + (size_t)h0 * kStatChunks * 3 * D, L);
+    for (int pass = 0; pass < (kBf16 ? 2 : 1); ++pass) {
+        if constexpr (kBf16) {
+            for (int h0 = 0; h0 < H; h0 += 32768) {      // grid.y is 16 bits wide
+                const int nh = (H - h0 < 32768) ? H - h0 : 32768;
+                hipLaunchKernelGGL((density_stats<D>), dim3(kStatChunks, nh), dim3(256), 0, st,
+                                   reinterpret_cast<const uint16_t *>(K) + (size_t)h0 * L * D,
+                                   p.stat + (size_t)h0 * kStatChunks * 3 * D, L, pass, p.cand + h0);
+            }
         }
-    }
-    for (int h0 = 0; h0 < H; h0 += 256) {
-        const int nh = (H - h0 < 256) ? H - h0 : 256;
-        ScaleChunk sc;
-        for (int i = 0; i < 256; ++i) {
-            // exponent scale log2(e)/sigma^2, so the sweep can use the hardware exp2
-            const double sg = (i < nh) ? (double)sigma_host[h0 + i] : 1.0;
-            sc.s[i] = (float)(1.4426950408889634 / (sg * sg));
+        for (int h0 = 0; h0 < H; h0 += 256) {
+            const int nh = (H - h0 < 256) ? H - h0 : 256;
+            ScaleChunk sc;
+            for (int i = 0; i < 256; ++i) {
+                // exponent scale log2(e)/sigma^2, so the sweep can use the hardware exp2
+                const double sg = (i < nh) ? (double)sigma_host[h0 + i] : 1.0;
+                sc.s[i] = (float)(1.4426950408889634 / (sg * sg));
+            }
+            hipLaunchKernelGGL((density_decide<D>), dim3(nh), dim3(D), 0, st, p, K, (size_t)L * D * sizeof(Elem), sc, h0,
+                               kBf16 ? 1 : 0);
         }
-        hipLaunchKernelGGL((density_decide<D>), dim3(nh), dim3(D), 0, st, p, K, (size_t)L * D * sizeof(Elem), sc, h0,
-                           kBf16 ? 1 : 0);
     }
     for (int h0 = 0; h0 < H; h0 += 32768) {      // grid.y is 16 bits wide
         const int nh = (H - h0 < 32768) ? H - h0 : 32768;
@@ -777,6 +796,7 @@ static void run_prep(const void *K, int H, int L, const float *sigma_host, const
         q.nsum += (size_t)h0 * (w.Lpad / 256);
         q.ext += (size_t)h0 * w.Lpad;
         q.Kc = reinterpret_cast<char *>(q.Kc) + (size_t)h0 * L * D * sizeof(Elem);
+        if (q.acc) q.acc += (size_t)h0 * w.Lpad;
         hipLaunchKernelGGL((density_prep<TR, D>), dim3(w.Lpad / 256, nh), dim3(256), 0, st,
                            reinterpret_cast<const Elem *>(K) + (size_t)h0 * L * D, q, L, w.Lpad);
     }
@@ -806,17 +826,15 @@ static hipError_t run_sym(const void *K, int H, int L, const float *sigma_host, 
     const DensityWs w = density_layout(H, L, D, true);
     char *base = reinterpret_cast<char *>(ws);
     run_prep<Bf16Tr, D>(K, H, L, sigma_host, w, base, st);
-    float *rowsum = reinterpret_cast<float *>(base + w.rowsum);
-    float *colpart = reinterpret_cast<float *>(base + w.colpart);
-    for (int h0 = 0; h0 < H; h0 += w.chunk) {
-        const int nh = (H - h0 < w.chunk) ? H - h0 : w.chunk;
+    unsigned long long *acc = reinterpret_cast<unsigned long long *>(base + w.acc);
+    const int chunk = kSymChunkHeads;            // heads per launch (keeps the grid within 2^31 workgroups)
+    for (int h0 = 0; h0 < H; h0 += chunk) {
+        const int nh = (H - h0 < chunk) ? H - h0 : chunk;
         const int total = nh * w.nB;
         hipLaunchKernelGGL((density_sym<D, RTW>), dim3(total), dim3(256), 0, st,
                            reinterpret_cast<const void *const *>(base + w.kbase), reinterpret_cast<const uint4 *>(base + w.ext),
-                           reinterpret_cast<const float *>(base + w.scale), rowsum, colpart, L, w.Lpad, w.nB, w.nBoth,
-                           h0, total);
-        hipLaunchKernelGGL(density_finish, dim3((L + 255) / 256, nh), dim3(256), 0, st, rowsum, colpart, rho, L,
-                           w.Lpad, w.nBoth, h0);
+                           reinterpret_cast<const float *>(base + w.scale), acc, L, w.Lpad, w.nB, w.nBoth, h0, total);
+        hipLaunchKernelGGL(density_finish, dim3((L + 255) / 256, nh), dim3(256), 0, st, acc, rho, L, w.Lpad, h0);
     }
     return hipGetLastError();
 }

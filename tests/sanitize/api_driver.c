@@ -35,6 +35,12 @@ int main(void)
     sigma[2] = 1e-30f;     /* 1/sigma^2 overflows the exponent scale */
     CHECK(ws_synapse_density(fake, WS_F32, H, 1000, 128, sigma, fake, fake, big, NULL) == WS_ERR_INVALID_ARG);
     sigma[2] = 2.0f;
+    int flagged = -1;
+    CHECK(ws_synapse_density_check(NULL, H, NULL, &flagged, NULL) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_density_check(fake, 0, NULL, &flagged, NULL) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_density_check(fake, H, NULL, NULL, NULL) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_density_is_symmetric(WS_BF16, 32768, 64) == 1 && ws_synapse_density_is_symmetric(WS_F32, 32768, 64) == 0);
+    CHECK(ws_synapse_density_is_symmetric(WS_BF16, 32768, 72) == 0);
     const int before = g_launches;
 
     CHECK(ws_synapse_select(fake, WS_BF16, H, 1000, 64, fake, 20, 0.5f, fake, NULL, fake, big, NULL) == WS_OK);

@@ -8,6 +8,8 @@ int g_launches = 0;
 namespace ws {
 
 size_t density_workspace_bytes(int H, int L, int, bool) { return (size_t)H * L * 16 + 256; }
+size_t density_estimate_offset() { return kDensityFlagBytes; }
+bool density_uses_symmetric(bool bf16, int L, int) { return bf16 && L >= 1024; }
 hipError_t launch_density(const void *, bool, int, int, int, const float *, float *, void *, hipStream_t)
 {
     ++g_launches;

@@ -220,11 +220,15 @@ def test_selection_grid_fits_the_device(lib, cus, per_cu):
 
 def test_density_workspace_size(lib):
     from paper_2601_01298_amd import binding as b
-    # the density workspace: a 16-byte record per key, and column partial sums capped near 4 GiB however many heads
+    # the density workspace: per key a 16-byte record and room for a translated copy of the row (bf16 keys), and
+    # column partial sums capped near 4 GiB however many heads
+    per_key = 16 + 64 * 2
     a = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 384, 32768, 64)
     c = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 4096, 32768, 64)
-    assert a >= 384 * 32768 * 16 and c - a < (4096 - 384) * 32768 * 16 + (2 << 30)
-    assert c < 4096 * 32768 * 16 + (5 << 30)
+    assert a >= 384 * 32768 * per_key and c - a < (4096 - 384) * 32768 * per_key + (2 << 30)
+    assert c < 4096 * 32768 * per_key + (5 << 30)
+    f = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_F32, 4, 1000, 64)     # fp32 keys: no copy
+    assert 4 * 1000 * 16 <= f < 4 * 1024 * 16 + (1 << 20)
 
 
 def test_bench_refuses_more_than_one_gpu():
