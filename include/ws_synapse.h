@@ -68,7 +68,8 @@ typedef void *ws_stream; /* hipStream_t */
  *     rho[h,i] = (1/L) * sum_{j<L} exp(-||K[h,i]-K[h,j]||^2 / (2 sigma[h]^2)),  j = i included,
  * no Gaussian normalising constant, so 1/L <= rho <= 1.
  *   K          dev  [H,L,d] keys, dtype `dt`
- *   sigma_host host [H] bandwidths, each finite and > 0 (read before the call returns)
+ *   sigma_host host [H] bandwidths, each finite and > 0 (read before the call returns); a bandwidth above
+ *              about 7e13 (where every kernel value is 1 to fp32 precision anyway) is WS_ERR_UNSUPPORTED
  *   rho        dev  [H,L] fp32, written
  *
  * Accuracy.  The squared distances come from a Gram product on the matrix cores, so one kernel term

@@ -73,6 +73,8 @@ ws_status ws_synapse_density(const void *K, ws_dtype dt, int H, int L, int d, co
         const double sg = (double)sigma_host[h];
         const float sc = (float)(1.4426950408889634 / (sg * sg));   // the exponent scale the kernel will use
         if (!(sg > 0.0) || !std::isfinite(sg) || !std::isfinite(sc) || sc <= 0.0f) return WS_ERR_INVALID_ARG;
+        // padded key slots carry -1e30 in place of -|k|^2/2: their kernel value must underflow to exactly 0
+        if (sc * 1.0e30f < 256.0f) return WS_ERR_UNSUPPORTED;
     }
     const hipError_t e = ws::launch_density(K, dt == WS_BF16, H, L, d, sigma_host, rho, workspace, (hipStream_t)stream);
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;

@@ -77,6 +77,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert D(fake, b.WS_BF16, 2, 100, 64, sig, fake, fake, 16, None) == b.WS_ERR_WORKSPACE
     assert D(fake, b.WS_BF16, 2, 100, 64, bad_sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
     assert D(fake, b.WS_BF16, 2, 100, 64, nan_sig, fake, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
+    huge_sig = (ctypes.c_float * 2)(1.0, 1e15)       # the padding sentinel would no longer underflow
+    assert D(fake, b.WS_BF16, 2, 100, 64, huge_sig, fake, fake, 1 << 30, None) == b.WS_ERR_UNSUPPORTED
     S = lib.ws_synapse_select
     assert S(fake, b.WS_BF16, 2, 100, 64, fake, 101, 0.5, fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
     assert S(fake, b.WS_BF16, 2, 100, 64, fake, 0, 0.5, fake, None, fake, 1 << 30, None) == b.WS_ERR_INVALID_ARG
