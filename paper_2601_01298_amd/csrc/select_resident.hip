@@ -55,6 +55,7 @@ struct Shared {
 // the L2 instead of (4 nwg)^2 * 16.  With `prefetch`, wave 0 touches the key row of this workgroup's
 // candidate after posting, so that it is in this die's L2 when the winner is fetched.
 // Returns false (for every thread of the workgroup) if the bounded wait expired.
+template <bool WIDE>
 __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, Shared &sh, unsigned long long *gslots,
                                          int nwg, int member, unsigned &seq, unsigned &dm_out, unsigned &hi_out,
                                          unsigned &lo_out, const uint16_t *pf_base, int D, int last_row, bool prefetch)
@@ -80,7 +81,8 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
         if (nwg > 1) {
             ++seq;
             const unsigned tag = seq % 255u + 1u;
-            unsigned long long *slot = gslots + (seq & 1u) * 2 * kMaxMembers;   // [kind][member]
+            constexpr int MS = WIDE ? kMaxMembersWide : kMaxMembers;
+            unsigned long long *slot = gslots + (seq & 1u) * 2 * MS;   // [kind][member]
             // Per-lane addresses are rebuilt from the lane id on every call: kept live across the
             // whole step loop they would be spilled and reloaded on this, the latency-critical path.
             int ln = lane;
@@ -88,7 +90,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
             if (ln < 2) {
                 const unsigned long long word =
                     ln == 0 ? (((unsigned long long)md << 32) | tag) : (((unsigned long long)mh << 32) | ml | tag);
-                __hip_atomic_store(slot + ln * kMaxMembers + member, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(slot + ln * MS + member, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             unsigned touched = 0u;
             if (prefetch && ln < D / 8) {
@@ -97,20 +99,50 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
                 touched = *reinterpret_cast<const volatile unsigned *>(pf_base + (size_t)cand * D + ln * 8);
             }
             const int who = ln & 31, kind = ln >> 5;
-            bool ok = who >= nwg;
             unsigned long long g = 0ull;
-            unsigned spins = 0;
-            while (true) {
-                if (!ok) {
-                    g = __hip_atomic_load(slot + kind * kMaxMembers + who, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ok = (unsigned)(g & 0xFFull) == tag;
+            if (!WIDE) {
+                bool ok = who >= nwg;
+                unsigned spins = 0;
+                while (true) {
+                    if (!ok) {
+                        g = __hip_atomic_load(slot + kind * MS + who, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = (unsigned)(g & 0xFFull) == tag;
+                    }
+                    if (__all(ok)) break;
+                    if (++spins > kSpinLimit) {
+                        good = false;
+                        break;
+                    }
+                    if (spins > 16) __builtin_amdgcn_s_sleep(1);
                 }
-                if (__all(ok)) break;
-                if (++spins > kSpinLimit) {
-                    good = false;
-                    break;
+            } else {
+                // up to 128 members: a lane polls members who, who + 32, who + 64, who + 96 and keeps the largest word
+                // (tag bits cleared; for the D maxima the low half is empty, so one 64-bit comparison serves both kinds)
+                unsigned pending = 0u;
+#pragma unroll
+                for (int q = 0; q < kMaxMembersWide / 32; ++q)
+                    if (who + 32 * q < nwg) pending |= 1u << q;
+                unsigned spins = 0;
+                while (true) {
+#pragma unroll
+                    for (int q = 0; q < kMaxMembersWide / 32; ++q) {
+                        if (pending & (1u << q)) {
+                            const unsigned long long v =
+                                __hip_atomic_load(slot + kind * MS + who + 32 * q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if ((unsigned)(v & 0xFFull) == tag) {
+                                pending &= ~(1u << q);
+                                const unsigned long long c = v & ~0xFFull;
+                                g = c > g ? c : g;
+                            }
+                        }
+                    }
+                    if (__all(pending == 0u)) break;
+                    if (++spins > kSpinLimit) {
+                        good = false;
+                        break;
+                    }
+                    if (spins > 16) __builtin_amdgcn_s_sleep(1);
                 }
-                if (spins > 16) __builtin_amdgcn_s_sleep(1);
             }
             if (who >= nwg || !good) g = 0ull;
             const unsigned gh = (unsigned)(g >> 32), gl = (unsigned)g & 0xFFFFFF00u;
@@ -145,7 +177,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
     return sh.abort == 0;
 }
 
-template <int D, int RREG, int RLDS>
+template <int D, int RREG, int RLDS, bool WIDE>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 select_resident(ResArgs a)
 {
@@ -162,14 +194,22 @@ select_resident(ResArgs a)
     __shared__ float sres_all[4][CAP];                          // per wave: the staged keys' exact distances
     __shared__ Shared sh;
 
+    // Workgroup ids are dealt to the 8 dies round-robin.  With a multiple of 8 heads in flight every head sits on one
+    // die; with 1, 2 or 4 a head takes 8, 4 or 2 whole dies (a 32 MiB head needs the registers and LDS of two).
     int group, member;
-    if ((a.groups & 7) == 0) {
+    {
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-        group = xcd * (a.groups >> 3) + j / a.wgpg;
-        member = j % a.wgpg;
-    } else {
-        group = blockIdx.x / a.wgpg;
-        member = blockIdx.x % a.wgpg;
+        const int dpg = a.groups <= 8 ? 8 / a.groups : 0;          // dies per head, if that divides evenly
+        if ((a.groups & 7) == 0) {
+            group = xcd * (a.groups >> 3) + j / a.wgpg;
+            member = j % a.wgpg;
+        } else if (dpg * a.groups == 8 && a.wgpg % dpg == 0) {
+            group = xcd / dpg;
+            member = xcd % dpg + dpg * j;
+        } else {
+            group = blockIdx.x / a.wgpg;
+            member = blockIdx.x % a.wgpg;
+        }
     }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = member * 4 + (tid >> 6);
@@ -180,7 +220,7 @@ select_resident(ResArgs a)
     // the keys a new landmark moves would otherwise pile up in one workgroup and make the others wait.
     const int rowbase = wv * 64 + lane;
     const int rstride = a.wgpg * 256;
-    unsigned long long *gslots = a.slots + (size_t)group * 4 * kMaxMembers;
+    unsigned long long *gslots = a.slots + (size_t)group * 4 * (WIDE ? kMaxMembersWide : kMaxMembers);
     const float alpha = a.alpha, oma = 1.0f - a.alpha;
     const float ninf = -__builtin_inff();
     unsigned seq = 0;
@@ -252,7 +292,7 @@ select_resident(ResArgs a)
         {
             unsigned mdm, mhi, mlo;
             const unsigned mine = wave_umax(0xFFFFFFFFu - __float_as_uint(rmin));
-            if (!head_max(mine, 0u, 0u, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
+            if (!head_max<WIDE>(mine, 0u, 0u, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, false)) goto bail;
             rmin = __uint_as_float(0xFFFFFFFFu - mdm);
         }
 #pragma unroll
@@ -543,7 +583,7 @@ select_resident(ResArgs a)
                         const unsigned clo = best >= 0.0f ? (0xFFFFFFu - (unsigned)bi) << 8 : 0u;
                         const unsigned whi = wave_umax(chi);
                         const unsigned wlo = wave_pick_lo(chi == whi, clo);
-                        if (!head_max(lbits, whi, wlo, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, true))
+                        if (!head_max<WIDE>(lbits, whi, wlo, sh, gslots, a.wgpg, member, seq, mdm, mhi, mlo, Kh, D, a.L - 1, true))
                             goto bail;
                         if (t == 0 || mdm == dprev) break;     // the guess was the true D_max
                         dprev = mdm;
@@ -585,10 +625,10 @@ __global__ void resident_clear(unsigned long long *slots, int n, int *fail)
     if (i == 0) *fail = 0;
 }
 
-template <int D, int RREG, int RLDS>
+template <int D, int RREG, int RLDS, bool WIDE = false>
 hipError_t run(const ResArgs &a, hipStream_t st)
 {
-    hipLaunchKernelGGL((select_resident<D, RREG, RLDS>), dim3(a.groups * a.wgpg), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((select_resident<D, RREG, RLDS, WIDE>), dim3(a.groups * a.wgpg), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
@@ -604,15 +644,16 @@ int instance_occupancy(int d, int rreg)
     int n = 0;
     hipError_t e = hipErrorInvalidValue;
     if (d == 64) {
-        if (rreg == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 1, 0>, 256, 0);
-        else if (rreg == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 2, 0>, 256, 0);
-        else if (rreg == 4) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 4, 0>, 256, 0);
+        if (rreg == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 1, 0, false>, 256, 0);
+        else if (rreg == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 2, 0, false>, 256, 0);
+        else if (rreg == 4) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<64, 4, 0, false>, 256, 0);
         else e = resident_ahead_occupancy(&n);
     } else {
-        if (rreg == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 1, 0>, 256, 0);
-        else if (rreg == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 2, 0>, 256, 0);
-        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 3, 1>, 256, 0);
+        if (rreg == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 1, 0, false>, 256, 0);
+        else if (rreg == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 2, 0, false>, 256, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_resident<128, 3, 1, false>, 256, 0);
     }
+    // (the wide instances differ from these only in the exchange's polling loop)
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return 2;
@@ -634,7 +675,8 @@ bool resident_select_shape(int H, int L, int d, const Chip &chip, ResidentShape 
     for (int i = 0; i < nopts; ++i) {
         const int R = opts[i][0] + opts[i][1];
         const int wgpg = (L + 256 * R - 1) / (256 * R);
-        if (wgpg > kMaxMembers) continue;
+        // more than 32 workgroups per head only in the instance with the most rows per lane (the wide exchange)
+        if (wgpg > (i == nopts - 1 ? kMaxMembersWide : kMaxMembers)) continue;
         const int occ = chip.wg_per_cu > 0 ? chip.wg_per_cu : instance_occupancy(d, opts[i][0]);
         const long long max_wg = (long long)chip.cus * occ;
         if (wgpg > max_wg) continue;                   // the group of one head could not be resident
@@ -642,6 +684,8 @@ bool resident_select_shape(int H, int L, int d, const Chip &chip, ResidentShape 
         if (groups > kMaxResidentGroups) groups = kMaxResidentGroups;
         if (groups > H) groups = H;
         if (groups >= 8) groups -= groups % 8;         // whole groups per die
+        else if (wgpg > kMaxMembers && groups == 3) groups = 2;   // whole dies per head: 1, 2 or 4 heads in flight
+        else if (wgpg > kMaxMembers && groups > 4) groups = 4;
         const int rounds = (H + groups - 1) / groups;
         if (!found || rounds < best.rounds) {
             best = ResidentShape{opts[i][0], opts[i][1], wgpg, groups, rounds};
@@ -655,7 +699,9 @@ size_t resident_select_workspace_bytes(int H)
 {
     // the flag block, then four tagged slots per member for every head that can be in flight on any chip
     const int groups = H < kMaxResidentGroups ? H : kMaxResidentGroups;
-    return kSelectFlagBytes + round_up((size_t)groups * 4 * kMaxMembers * sizeof(unsigned long long), 256);
+    const int wide = H < 16 ? H : 16;        // heads in flight with more than 32 workgroups each: fewer than 16 on any chip
+    return kSelectFlagBytes + round_up(((size_t)groups * 4 * kMaxMembers + (size_t)wide * 4 * kMaxMembersWide) *
+                                           sizeof(unsigned long long), 256);
 }
 
 hipError_t launch_select_resident(const void *K, int H, int L, int d, const float *rho, int k, float alpha,
@@ -668,7 +714,8 @@ hipError_t launch_select_resident(const void *K, int H, int L, int d, const floa
     a.score_out = score_out;
     a.fail = reinterpret_cast<int *>(ws);
     a.slots = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(ws) + kSelectFlagBytes);
-    const size_t nslots = (size_t)s.groups * 4 * kMaxMembers;
+    const bool wide = s.wgpg > kMaxMembers;
+    const size_t nslots = (size_t)s.groups * 4 * (wide ? kMaxMembersWide : kMaxMembers);
     a.H = H;
     a.L = L;
     a.k = k;
@@ -677,6 +724,10 @@ hipError_t launch_select_resident(const void *K, int H, int L, int d, const floa
     a.alpha = alpha;
     hipLaunchKernelGGL(resident_clear, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, st, a.slots, (int)nslots,
                        a.fail);
+    if (wide) {
+        if (s.groups > 16) return hipErrorInvalidValue;
+        return d == 64 ? run<64, 6, 2, true>(a, st) : run<128, 3, 1, true>(a, st);
+    }
     if (d == 64) {
         if (s.rreg == 1) return run<64, 1, 0>(a, st);
         if (s.rreg == 2) return run<64, 2, 0>(a, st);

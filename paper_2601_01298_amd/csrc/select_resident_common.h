@@ -9,7 +9,8 @@
 namespace ws {
 namespace resident {
 
-constexpr int kMaxMembers = 32;             // workgroups cooperating on one head
+constexpr int kMaxMembers = 32;             // workgroups cooperating on one head (one slot polled per lane) ...
+constexpr int kMaxMembersWide = 128;        // ... and in the wide instances for heads that need more (four per lane)
 constexpr unsigned kSpinLimit = 1u << 22;
 
 struct ResArgs {
@@ -17,7 +18,7 @@ struct ResArgs {
     const float *rho;
     int32_t *idx;
     float *score_out;
-    unsigned long long *slots;   // [groups][2 phases][2 kinds][kMaxMembers]
+    unsigned long long *slots;   // [groups][2 phases][2 kinds][kMaxMembers, or kMaxMembersWide in a wide instance]
     int *fail;
     int H, L, k;
     int groups, wgpg;            // heads in flight, workgroups per head

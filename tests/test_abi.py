@@ -161,12 +161,12 @@ def test_bad_arguments_of_the_next_steps_are_rejected_on_the_host(lib):
 def test_selection_kernel_choice_is_host_logic(lib):
     """Which selection kernel a shape gets is decided on the host from the sizes and the device's shape: heads
     whose keys fit the chip's registers and LDS (32 headline heads at a time) stay on chip, fp32 keys and
-    oversized heads stream.  No environment variable takes part."""
+    heads beyond 128 workgroups' worth of registers and LDS stream.  No environment variable takes part."""
     import subprocess
     import sys
     from paper_2601_01298_amd import binding as b
     from paper_2601_01298_amd import synthetic as syn
-    expect = {1: False, 2: True, 3: True, 4: True, 5: False}
+    expect = {1: False, 2: True, 3: True, 4: True, 5: True}
     for cfg, w in syn.WORKLOADS.items():
         dt = b.WS_BF16 if w.dtype == "bf16" else b.WS_F32
         assert b.ws_synapse_select_is_resident(dt, w.H, w.L, w.d) == expect[cfg], w.name
@@ -174,8 +174,10 @@ def test_selection_kernel_choice_is_host_logic(lib):
     assert not b.ws_synapse_select_plan("stream", b.WS_BF16, 384, 32768, 64).resident
     with pytest.raises(b.WsError):
         b.ws_synapse_select_plan("resident", b.WS_F32, 1, 512, 64)          # fp32 keys never sit on chip
+    p5 = b.ws_synapse_select_plan("resident", b.WS_BF16, 8, 131072, 128)    # a 32 MiB head: 128 workgroups on two dies
+    assert (p5.heads_in_flight, p5.workgroups_per_head, p5.rows_in_registers, p5.rows_in_lds) == (4, 128, 3, 1)
     with pytest.raises(b.WsError):
-        b.ws_synapse_select_plan("resident", b.WS_BF16, 8, 131072, 128)     # a head larger than 32 workgroups hold
+        b.ws_synapse_select_plan("resident", b.WS_BF16, 8, 300000, 128)     # a head larger than 128 workgroups hold
     code = ("import os; os.environ['WS_SYNAPSE_SELECT']='stream'; from paper_2601_01298_amd import binding as b; "
             "print(int(b.ws_synapse_select_is_resident(b.WS_BF16, 384, 32768, 64)))")
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=ROOT, timeout=120)
@@ -207,7 +209,9 @@ def test_selection_grid_fits_the_device(lib, cus, per_cu):
                 if p.resident:
                     assert dt == b.WS_BF16 and kernel != "stream" and p.threads == 256
                     assert p.workgroups_per_head * 256 * (p.rows_in_registers + p.rows_in_lds) >= L
-                    assert p.workgroups_per_head <= 32
+                    assert p.workgroups_per_head <= 128
+                    if p.workgroups_per_head > 32:
+                        assert p.heads_in_flight in (1, 2, 4, 8, 16)      # whole dies per head
                 else:
                     assert kernel != "resident" and p.threads == 512 and p.workgroups_per_head <= 64
     # the headline on the full chip: 32 heads in flight, 16 workgroups each, 6 + 2 rows per lane

@@ -44,6 +44,7 @@ def test_long_context_gqa_full_size(oracle):
     plan = ws.ws_synapse_select_plan("auto", ws.WS_BF16, w.H, w.L, w.d)
     rho = ws.ws_synapse_density(K, sigma)
     idx, score = ws.ws_synapse_select(K, rho, w.k, w.alpha, want_score=True)
+    idx_stream = ws.ws_synapse_select(K, rho, w.k, w.alpha, kernel="stream")       # the other kernel, same inputs
     Ks, Vs = ws.ws_synapse_gather(K, V, idx)
     O = ws.ws_synapse_attend(Q, Ks, Vs)
     torch.cuda.synchronize()
@@ -85,6 +86,7 @@ def test_long_context_gqa_full_size(oracle):
         err = float(np.abs(rho_h[h] / rho_ref - 1).max())
         ref, _, gap = oracle.select(Kh[h], rho_ref, w.k, w.alpha)
         forks = check_indices(oracle, Kh[h], rho_ref, w.k, w.alpha, idx_h[h], ref)
+        forks_s = check_indices(oracle, Kh[h], rho_ref, w.k, w.alpha, idx_stream[h].cpu().numpy(), ref)
         ks, vs = oracle.gather(Kh[h], Vh[h], idx_h[h])
         assert np.array_equal(Ks[h].float().cpu().numpy(), ks) and np.array_equal(Vs[h].float().cpu().numpy(), vs)
         O_ref = oracle.attend(Qh[:, h * g:(h + 1) * g], ks[None], vs[None])
@@ -93,6 +95,6 @@ def test_long_context_gqa_full_size(oracle):
         forks_total += forks
         ties_total += ties
         print(f"head {h}: density rel err over all {w.L} keys {err:.2e}; oracle steps under tie tolerance {ties}, "
-              f"forks {forks}; attention rel err (N={w.N}, {g} query heads) {aerr:.2e}", flush=True)
+              f"forks {forks} (streaming kernel: {forks_s}); attention rel err (N={w.N}, {g} query heads) {aerr:.2e}", flush=True)
         assert err <= 5e-5 and aerr <= 2e-3
     print(f"long-context config: {ties_total} near-tie steps survived, {forks_total} near-tie forks on 2 heads", flush=True)

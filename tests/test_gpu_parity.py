@@ -206,23 +206,31 @@ def test_select_with_near_tie_forks(ws, oracle, cfg, H, L, k, select_kernel):
         print(f"cfg{cfg} head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
 
 
-def test_select_streaming_at_long_context_size(ws, oracle):
-    """Head size of the long-context configuration (L = 131072, d = 128: too large to sit on chip, so
-    the streaming kernel with 64 workgroups per head runs).  A full oracle density at this size takes
-    minutes, so the density handed to both sides is synthetic (any positive array is a valid input of
-    the selection); the chain is shortened to k = 200."""
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("d,cfg", [(128, 5), (64, 3)])
+def test_select_at_long_context_head_size(ws, oracle, d, cfg):
+    """Head size of the long-context configuration (L = 131072): both kernels.  Such a head is too large for 32
+    workgroups, so the on-chip kernel runs its wide instances (128 workgroups per head on two dies at d = 128, 64 at
+    d = 64) and the streaming kernel 64 workgroups per head.  A full oracle density at this size takes minutes, so
+    the density handed to both sides is synthetic (any positive array is a valid input of the selection); the chain
+    is shortened to k = 200."""
     import torch
-    w = variant(5, H=2, L=131072, k=200)
+    w = variant(cfg, H=2, Hq=2, L=131072, k=200, d=d) if cfg == 5 else variant(cfg, H=2, Hq=2, L=131072, k=200)
+    assert w.d == d
     rng = np.random.default_rng(77)
     K = np.stack([syn.cloud(w, h, syn.TENSOR_K) for h in range(w.H)])
     rho = rng.uniform(0.05, 1.0, size=(w.H, w.L)).astype(np.float32)
     Kd = to_device(K, w.dtype)
-    assert not ws.ws_synapse_select_is_resident(ws.WS_BF16, w.H, w.L, w.d)
-    idx = ws.ws_synapse_select(Kd, torch.from_numpy(rho).cuda(), w.k, w.alpha).cpu().numpy()
-    for h in range(w.H):
-        ref, _, gap = oracle.select(K[h], rho[h], w.k, w.alpha)
-        forks = check_indices(oracle, K[h], rho[h], w.k, w.alpha, idx[h], ref)
-        print(f"L=131072 head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
+    plan = ws.ws_synapse_select_plan("auto", ws.WS_BF16, w.H, w.L, w.d)
+    assert plan.resident and plan.workgroups_per_head == (128 if d == 128 else 64)
+    assert not ws.ws_synapse_select_plan("stream", ws.WS_BF16, w.H, w.L, w.d).resident
+    refs = [oracle.select(K[h], rho[h], w.k, w.alpha) for h in range(w.H)]
+    for kernel in ("auto", "stream"):
+        idx = ws.ws_synapse_select(Kd, torch.from_numpy(rho).cuda(), w.k, w.alpha, kernel=kernel).cpu().numpy()
+        for h in range(w.H):
+            ref, _, gap = refs[h]
+            forks = check_indices(oracle, K[h], rho[h], w.k, w.alpha, idx[h], ref)
+            print(f"L=131072 d={d} {kernel} head {h}: oracle steps below tie tolerance {(gap < TIE_TOL).sum()}, forks {forks}")
 
 
 _scale_out_oracle = {}
