@@ -658,7 +658,9 @@ int instance_occupancy(int d, int rreg)
         (void)hipGetLastError();
         return 2;
     }
-    return n;
+    // The answer guards against a device that holds FEWER than the two the launch shapes are tuned for; where more
+    // would fit (the small instances), more workgroups per head only make the exchange slower.
+    return n < 2 ? n : 2;
 }
 
 }  // namespace

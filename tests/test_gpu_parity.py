@@ -338,10 +338,12 @@ def test_select_edge_cases_bf16(ws, oracle, select_kernel):
     assert one.cpu().numpy().tolist() == [[0], [0]]
 
 
-@pytest.mark.parametrize("cfg,H,L,k,rows", [(2, 40, 4096, 30, "2 rows per lane"), (2, 96, 4096, 30, "4 rows per lane"),
-                                            (2, 136, 4096, 30, "6 + 2 rows per lane"), (4, 40, 4096, 30, "d=128, 2 rows"),
-                                            (4, 72, 4096, 30, "d=128, 3 + 1 rows")])
-def test_select_resident_every_instance(ws, oracle, cfg, H, L, k, rows):
+@pytest.mark.parametrize("cfg,H,L,k,rows,split", [(2, 40, 4096, 30, "2 rows per lane", (2, 0)),
+                                                  (2, 96, 4096, 30, "4 rows per lane", (4, 0)),
+                                                  (2, 136, 4096, 30, "6 + 2 rows per lane", (6, 2)),
+                                                  (4, 40, 4096, 30, "d=128, 2 rows", (2, 0)),
+                                                  (4, 72, 4096, 30, "d=128, 3 + 1 rows", (3, 1))])
+def test_select_resident_every_instance(ws, oracle, cfg, H, L, k, rows, split):
     """The on-chip kernel is compiled for several splits of a head (key rows per lane in registers + in
     LDS); the library takes the one with the fewest passes over the heads.  These head counts make it take
     each split in turn (with L = 4096: 16, 8, 4 or 2 workgroups per head).  Heads are copies of 4 clouds:
@@ -351,7 +353,8 @@ def test_select_resident_every_instance(ws, oracle, cfg, H, L, k, rows):
     K = np.stack([base[h % 4] for h in range(H)])
     sigma = [float(syn.bandwidth(base[h % 4])) for h in range(H)]
     Kd = to_device(K, w.dtype)
-    assert ws.ws_synapse_select_is_resident(ws.WS_BF16, H, L, w.d)
+    plan = ws.ws_synapse_select_plan("resident", ws.WS_BF16, H, L, w.d)
+    assert plan.resident and (plan.rows_in_registers, plan.rows_in_lds) == split, "this head count no longer selects the split"
     rho = ws.ws_synapse_density(Kd, sigma)
     idx = ws.ws_synapse_select(Kd, rho, k, w.alpha, kernel="resident").cpu().numpy()
     for h in range(4, H):
