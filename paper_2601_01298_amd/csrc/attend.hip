@@ -254,6 +254,12 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
         // probabilities as bf16 hi + bf16 lo (16 significant bits): one bf16 alone would cost up to
         // 2^-9 relative error per weight, which is the whole error budget of the output
         uint32_t pkh[8], pkl[8];
+        // (-1, 0) and (0, -1) as bf16 pairs, kept in registers: written as an immediate operand the first one is
+        // encoded as the inline constant -1.0, which this instruction reads as the fp32 pattern, i.e. as (0, -1)
+        uint32_t c10 = 0x0000BF80u, c01 = 0xBF800000u;
+        asm volatile("" : "+v"(c10), "+v"(c01));
+        const bf16x2_t kMinusOneZero = __builtin_bit_cast(bf16x2_t, c10);
+        const bf16x2_t kZeroMinusOne = __builtin_bit_cast(bf16x2_t, c01);
         float psum = 0.0f;
         const float nmref = -mref;
 #pragma unroll
@@ -262,11 +268,13 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
             pv[0] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w], scale_log2, nmref));
             pv[1] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w + 1], scale_log2, nmref));
             psum += pv[0] + pv[1];
-            const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, bf16x2_t));
+            const bf16x2_t hi2 = __builtin_convertvector(pv, bf16x2_t);
+            // what the bf16 pair leaves of each weight, straight from the packed pair: p - hi.x * 1 - hi.y * 0 in one
+            // dot-product instruction (exact: the difference has at most 16 significant bits)
             f32x2_t rest;
-            rest[0] = pv[0] - __uint_as_float(hi << 16);
-            rest[1] = pv[1] - __uint_as_float(hi & 0xFFFF0000u);
-            pkh[w] = hi;
+            rest[0] = __builtin_amdgcn_fdot2_f32_bf16(hi2, kMinusOneZero, pv[0], false);
+            rest[1] = __builtin_amdgcn_fdot2_f32_bf16(hi2, kZeroMinusOne, pv[1], false);
+            pkh[w] = __builtin_bit_cast(uint32_t, hi2);
             pkl[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
         }
         lrun += psum;
