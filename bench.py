@@ -92,6 +92,8 @@ def main() -> int:
     dev = K.device
     ws_density = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_DENSITY, dt, w.H, w.L, w.d), dtype=torch.uint8, device=dev)
     ws_select = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_SELECT, dt, w.H, w.L, w.d, w.k), dtype=torch.uint8, device=dev)
+    n_att = ws.ws_synapse_workspace_bytes(ws.WS_OP_ATTEND, dt, w.H, 1, w.d, w.k, w.N, w.Hq)
+    ws_attend = torch.empty(n_att, dtype=torch.uint8, device=dev) if n_att else None
     rho = torch.empty((w.H, w.L), dtype=torch.float32, device=dev)
     idx = torch.empty((w.H, w.k), dtype=torch.int32, device=dev)
     Ks = torch.empty((w.H, w.k, w.d), dtype=K.dtype, device=dev)
@@ -113,7 +115,7 @@ def main() -> int:
         ws.ws_synapse_gather(K, V, idx, Ks=Ks, Vs=Vs)
         if ev:
             ev[3].record()
-        ws.ws_synapse_attend(Q, Ks, Vs, O=O)
+        ws.ws_synapse_attend(Q, Ks, Vs, O=O, workspace=ws_attend)
         if ev:
             ev[4].record()
 

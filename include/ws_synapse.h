@@ -53,7 +53,8 @@ typedef enum {
 typedef enum { WS_F32 = 0, WS_BF16 = 1, WS_DTYPE_INT_RANGE = 0x7fffffff } ws_dtype;
 
 typedef enum {
-    WS_OP_DENSITY = 0, WS_OP_SELECT = 1, WS_OP_GATHER = 2, WS_OP_ATTEND = 3,
+    WS_OP_DENSITY = 0, WS_OP_SELECT = 1, WS_OP_GATHER = 2,
+    WS_OP_ATTEND = 3,          /* H = KV heads, Hq = query heads (a multiple of H), k, N; L is not used */
     WS_OP_ATTENTION_MASS = 4,  /* H = G*Hkv heads, Hq = query heads per group times G */
     WS_OP_DENSITY_APPEND = 5,  /* k = m appended rows */
     WS_OP_INJECT = 6,          /* k = m injected rows */
@@ -208,7 +209,9 @@ ws_status ws_synapse_gather(const void *K, const void *V, ws_dtype dt, int H, in
  *     O[n,q,:] = softmax_t( scale * Q[n,q,:] . Ks[q/g,t,:] ) . Vs[q/g,:,:],   g = Hq/Hkv, t < k
  * no mask (every landmark is past context); all agents read the same synapse.
  *   Q dev [N,Hq,d];  Ks, Vs dev [Hkv,k,d];  Hq % Hkv == 0;  scale <= 0 means 1/sqrt(d)
- *   O dev [N,Hq,d] fp32, written.  workspace may be NULL when the reported size is 0.
+ *   O dev [N,Hq,d] fp32, written.  workspace may be NULL when the reported size is 0 (it is, unless few heads
+ *   meet many landmarks: then the landmark range is split over several workgroups per head, whose partial rows
+ *   pass through the workspace and are merged by a second small kernel; the split depends on the sizes only).
  */
 ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dtype dt,
                             int N, int Hq, int Hkv, int k, int d, float scale, float *O,

@@ -32,7 +32,6 @@ extern "C" {
 
 size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, int k, int N, int Hq)
 {
-    (void)N;
     if (check_common(dt, d) != WS_OK) return (size_t)-1;
     switch (op) {
     case WS_OP_DENSITY:
@@ -42,8 +41,11 @@ size_t ws_synapse_workspace_bytes(ws_op op, ws_dtype dt, int H, int L, int d, in
         if (H < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
         return ws::select_workspace_bytes(H, L, d, dt == WS_BF16);
     case WS_OP_GATHER:
-    case WS_OP_ATTEND:
         return 0;
+    case WS_OP_ATTEND:
+        // H = KV heads, Hq = query heads, L is not used
+        if (H < 1 || Hq < 1 || N < 1 || k < 1 || Hq % H != 0) return (size_t)-1;
+        return ws::attend_workspace_bytes(dt == WS_BF16, N, Hq, H, k, d);
     case WS_OP_ATTENTION_MASS:
         // H = KV heads in all groups, Hq = query heads in all groups: per-head logits and tile partials
         if (H < 1 || Hq < 1 || L < 1 || L >= kMaxL) return (size_t)-1;
@@ -206,8 +208,6 @@ ws_status ws_synapse_gather(const void *K, const void *V, ws_dtype dt, int H, in
 ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dtype dt, int N, int Hq, int Hkv, int k,
                             int d, float scale, float *O, void *workspace, size_t workspace_bytes, ws_stream stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     ws_status s = check_common(dt, d);
     if (s != WS_OK) return s;
     if (!Q || !Ks || !Vs || !O || N < 1 || Hq < 1 || Hkv < 1 || k < 1) return WS_ERR_INVALID_ARG;
@@ -216,7 +216,10 @@ ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dt
     if (!aligned(Q, 16) || !aligned(Ks, 16) || !aligned(Vs, 16) || !aligned(O, 16)) return WS_ERR_INVALID_ARG;
     if (!std::isfinite(scale)) return WS_ERR_INVALID_ARG;
     if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)d);
-    const hipError_t e = ws::launch_attend(Q, Ks, Vs, dt == WS_BF16, N, Hq, Hkv, k, d, scale, O, (hipStream_t)stream);
+    s = check_ws(workspace, workspace_bytes, ws::attend_workspace_bytes(dt == WS_BF16, N, Hq, Hkv, k, d));
+    if (s != WS_OK) return s;
+    const hipError_t e = ws::launch_attend(Q, Ks, Vs, dt == WS_BF16, N, Hq, Hkv, k, d, scale, O, workspace,
+                                           (hipStream_t)stream);
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
 

@@ -91,7 +91,8 @@ __device__ __forceinline__ void wait_vmcnt()
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
 attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, const uint16_t *__restrict__ Vs,
-            float *__restrict__ O, int N, int Hq, int Hkv, int k, float scale_log2, int parts)
+            float *__restrict__ O, int N, int Hq, int Hkv, int k, float scale_log2, int parts, int splits,
+            float *__restrict__ partial)
 {
     constexpr int NK = D / 16;   // k-steps of the score product
     constexpr int NP = D / 64;   // 64-wide spans of head dimensions, each an even and an odd tile
@@ -106,14 +107,17 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     constexpr int XCH = 2 * (NO + 2) * 64 * 4 / 16;                  // the merge area, in 16-byte units
     __shared__ uint4 smem[NBUF * STG > XCH ? NBUF * STG : XCH];
     // workgroup id -> (head, part): parts of one head sit on one die (ids are dealt to the 8 dies round-robin)
+    // With few heads and many landmarks the landmark range is also split over `splits` workgroups (consecutive ids),
+    // each leaving a normalised partial result that a second kernel merges.
+    const int sp = blockIdx.x % splits, bid = blockIdx.x / splits;
     int h, part;
     if ((Hkv & 7) == 0) {
-        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int xcd = bid & 7, j = bid >> 3;
         h = (j / parts) * 8 + xcd;
         part = j % parts;
     } else {
-        h = blockIdx.x / parts;
-        part = blockIdx.x % parts;
+        h = bid / parts;
+        part = bid % parts;
     }
     const int g = Hq / Hkv;
     const int M = N * g;         // query rows that read this KV head
@@ -138,8 +142,10 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     float mref = -__builtin_inff();   // reference maximum (log2 units) the weights are taken against
     float lrun = 0.0f;
 
-    const int nT = (k + 31) / 32;
-    const int tA = (nT + 1) / 2;      // half 0 walks tiles [0, tA), half 1 [tA, nT): tA stages, the last may lack half 1
+    const int nTall = (k + 31) / 32;
+    const int T0 = (int)((long long)sp * nTall / splits);             // this workgroup's tiles: [T0, nT)
+    const int nT = (int)((long long)(sp + 1) * nTall / splits);
+    const int tA = (nT - T0 + 1) / 2;  // half 0 walks tiles [T0, T0 + tA), half 1 [T0 + tA, nT): tA stages, the last may lack half 1
 
     // ---- the copy: thread `tid` moves piece q = tid + 256 i of a tile, i.e. row q / CH, LDS slot q % CH; the K tile's
     // slot c of row r holds piece c ^ (r & 7) (256 / CH rows further on the swizzle is the same: a multiple of 8).
@@ -149,8 +155,8 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     const unsigned kpiece = (unsigned)(((tid % CH) ^ (crow & 7)) * 16);
     const unsigned vpiece = (unsigned)((tid % CH) * 16);
     const unsigned last = (unsigned)(k - 1) * RB;
-    unsigned off0 = (unsigned)crow * RB;                             // this thread's first row of the next stage, half 0 ...
-    unsigned off1 = (unsigned)(tA * 32 + crow) * RB;                 // ... and half 1 (may lie past the end: clamped, never read)
+    unsigned off0 = (unsigned)(T0 * 32 + crow) * RB;                 // this thread's first row of the next stage, half 0 ...
+    unsigned off1 = (unsigned)((T0 + tA) * 32 + crow) * RB;          // ... and half 1 (may lie past the end: clamped, never read)
     auto issue = [&](int bi) {                                       // bi: stage buffer, a compile-time constant at every call
         uint4 *buf = smem + bi * STG + wave * 64;
 #pragma unroll
@@ -201,7 +207,7 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
         // ... and so have everybody's; all waves are through with the buffer that is refilled next
         lds_only_barrier();
         if (sidx + PF < tA) issue((bi + PF) % NBUF);
-        const int t = half ? tA + sidx : sidx;
+        const int t = T0 + (half ? tA + sidx : sidx);
         if (!tile_live || t >= nT) return;             // wave-uniform
         const int t0 = t * 32;
         const uint4 *sK = smem + bi * STG + (half * 2 + 0) * TP;
@@ -336,7 +342,9 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[i][r] = oacc[i][r] * g0 + xch[wt][i * 16 + r][lane] * g1;
         if (valid) {
-            float *orow = O + ((size_t)agent * Hq + qh) * D;
+            // one workgroup per landmark range: the result; several: a partial row [D values, maximum, denominator, pad]
+            const size_t rowid = (size_t)agent * Hq + qh;
+            float *orow = splits == 1 ? O + rowid * D : partial + ((size_t)sp * N * Hq + rowid) * (D + 4);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
 #pragma unroll
@@ -348,8 +356,36 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
                     *reinterpret_cast<float4 *>(dst + 4) = make_float4(oacc[2 * p][4 * b + 2], oacc[2 * p + 1][4 * b + 2],
                                                                        oacc[2 * p][4 * b + 3], oacc[2 * p + 1][4 * b + 3]);
                 }
+            if (splits > 1 && hb == 0) *reinterpret_cast<float2 *>(orow + D) = make_float2(mm, l);
         }
     }
+}
+
+// Merge of the partial rows of a split landmark range: O = sum_s w_s O_s / sum_s w_s, w_s = l_s 2^(m_s - max m).
+template <int D>
+__global__ void __launch_bounds__(256)
+attend_merge(const float *__restrict__ partial, float *__restrict__ O, long long rows, int splits)
+{
+    constexpr int TPR = D / 4;                     // threads per row, a float4 each
+    const long long row = (long long)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    const int c = threadIdx.x % TPR;
+    if (row >= rows) return;
+    float mmax = -__builtin_inff();
+    for (int s = 0; s < splits; ++s) mmax = fmaxf(mmax, partial[((size_t)s * rows + row) * (D + 4) + D]);
+    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    float wsum = 0.0f;
+    for (int s = 0; s < splits; ++s) {
+        const float *pr = partial + ((size_t)s * rows + row) * (D + 4);
+        const float w = pr[D + 1] * __builtin_amdgcn_exp2f(pr[D] - mmax);
+        const float4 v = *reinterpret_cast<const float4 *>(pr + 4 * c);
+        acc.x = fmaf(w, v.x, acc.x);
+        acc.y = fmaf(w, v.y, acc.y);
+        acc.z = fmaf(w, v.z, acc.z);
+        acc.w = fmaf(w, v.w, acc.w);
+        wsum += w;
+    }
+    const float inv = 1.0f / wsum;
+    *reinterpret_cast<float4 *>(O + row * D + 4 * c) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
 template <int D>
@@ -414,26 +450,59 @@ attend_f32(const float *__restrict__ Q, const float *__restrict__ Ks, const floa
 
 }  // namespace
 
+// Landmark-range splits for a launch: with enough (head, query tile pair) workgroups to fill the chip, one; otherwise as
+// many as bring the grid to about 512 workgroups, each split keeping at least four landmark tiles.  The choice depends
+// on the sizes only, so the result (the merge order) is the same on every device.
+static int attend_splits(long long wgs, int k)
+{
+    const int nT = (k + 31) / 32;
+    if (wgs >= 384 || nT < 8) return 1;
+    long long s = (512 + wgs - 1) / wgs;
+    if (s > nT / 4) s = nT / 4;
+    if (s > 16) s = 16;
+    return s < 1 ? 1 : (int)s;
+}
+
+size_t attend_workspace_bytes(bool bf16, int N, int Hq, int Hkv, int k, int d)
+{
+    if (!bf16 || Hkv < 1 || Hq % Hkv != 0) return 0;
+    const long long M = (long long)N * (Hq / Hkv);
+    const int s = attend_splits((M + 63) / 64 * Hkv, k);
+    return s == 1 ? 0 : round_up((size_t)s * N * Hq * (d + 4) * sizeof(float), 256);
+}
+
 hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq, int Hkv, int k,
-                         int d, float scale, float *O, hipStream_t st)
+                         int d, float scale, float *O, void *ws, hipStream_t st)
 {
     if (bf16) {
         const int g = Hq / Hkv;
         const long long M = (long long)N * g;
         const long long parts = (M + 63) / 64;                 // workgroups (2 query tiles each) per head
-        const long long blocks = parts * Hkv;
+        const int splits = attend_splits(parts * Hkv, k);
+        const long long blocks = parts * Hkv * splits;
         if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
         const dim3 grid((unsigned)blocks);
         const float sl2 = scale * 1.4426950408889634f;
         const uint16_t *q = reinterpret_cast<const uint16_t *>(Q);
         const uint16_t *ks = reinterpret_cast<const uint16_t *>(Ks);
         const uint16_t *vs = reinterpret_cast<const uint16_t *>(Vs);
-        if (d == 64)
-            hipLaunchKernelGGL(attend_bf16<64>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts);
-        else if (d == 128)
-            hipLaunchKernelGGL(attend_bf16<128>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts);
-        else
+        float *part = reinterpret_cast<float *>(ws);
+        const long long rows = (long long)N * Hq;
+        if (d == 64) {
+            hipLaunchKernelGGL(attend_bf16<64>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts, splits,
+                               part);
+            if (splits > 1)
+                hipLaunchKernelGGL(attend_merge<64>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, part, O, rows,
+                                   splits);
+        } else if (d == 128) {
+            hipLaunchKernelGGL(attend_bf16<128>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts, splits,
+                               part);
+            if (splits > 1)
+                hipLaunchKernelGGL(attend_merge<128>, dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, st, part, O, rows,
+                                   splits);
+        } else {
             return hipErrorInvalidValue;
+        }
     } else {
         const long long blocks = (long long)N * Hq;
         if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;

@@ -106,8 +106,10 @@ hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int
                          const int32_t *idx, int k, void *Ks, void *Vs, hipStream_t st);
 
 // ---- attention -----------------------------------------------------------------------
+// partial rows of a split landmark range (0 when the range is not split)
+size_t attend_workspace_bytes(bool bf16, int N, int Hq, int Hkv, int k, int d);
 hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq,
-                         int Hkv, int k, int d, float scale, float *O, hipStream_t st);
+                         int Hkv, int k, int d, float scale, float *O, void *ws, hipStream_t st);
 
 // ---- steps next to the hot path -------------------------------------------------------
 bool mass_supported(int Hkv, int Hq);

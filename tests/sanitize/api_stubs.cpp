@@ -39,7 +39,11 @@ hipError_t launch_gather(const void *, const void *, int, int, int, const int32_
     ++g_launches;
     return hipSuccess;
 }
-hipError_t launch_attend(const void *, const void *, const void *, bool, int, int, int, int, int, float, float *,
+size_t attend_workspace_bytes(bool bf16, int N, int Hq, int Hkv, int k, int d)
+{
+    return (bf16 && Hkv <= 8 && k >= 2048) ? (size_t)4 * N * Hq * (d + 4) * 4 : 0;
+}
+hipError_t launch_attend(const void *, const void *, const void *, bool, int, int, int, int, int, float, float *, void *,
                          hipStream_t)
 {
     ++g_launches;

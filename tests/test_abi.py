@@ -48,7 +48,12 @@ def test_status_strings(lib):
 def test_workspace_query(lib):
     from paper_2601_01298_amd import binding as b
     assert b.ws_synapse_workspace_bytes(b.WS_OP_GATHER, b.WS_BF16, 4, 100, 64) == 0
-    assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTEND, b.WS_BF16, 4, 100, 64) == 0
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTEND, b.WS_BF16, 384, 1, 64, k=655, N=100, Hq=384) == 0
+    # few heads, many landmarks: partial rows of a split landmark range (4 splits x 8192 rows x (128 + 4) floats)
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTEND, b.WS_BF16, 8, 1, 128, k=2621, N=256, Hq=32) == 4 * 8192 * 132 * 4
+    assert b.ws_synapse_workspace_bytes(b.WS_OP_ATTEND, b.WS_F32, 8, 1, 128, k=2621, N=256, Hq=32) == 0
+    with pytest.raises(b.WsError):
+        b.ws_synapse_workspace_bytes(b.WS_OP_ATTEND, b.WS_BF16, 4, 1, 64, k=10, N=4, Hq=6)
     n1 = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 4, 1000, 64)
     n2 = b.ws_synapse_workspace_bytes(b.WS_OP_DENSITY, b.WS_BF16, 8, 1000, 64)
     assert 0 < n1 < n2 and n1 >= 4 * 1000 * 16
@@ -118,6 +123,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert A(fake, fake, fake, b.WS_BF16, 0, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
     assert A(fake, fake, fake, b.WS_BF16, 4, 4, 4, 10, 64, float("inf"), fake, None, 0, None) == b.WS_ERR_INVALID_ARG
     assert A(fake, fake, None, b.WS_BF16, 4, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
+    assert A(fake, fake, fake, b.WS_BF16, 256, 32, 8, 2621, 128, 0.0, fake, None, 0, None) == b.WS_ERR_WORKSPACE   # split range
 
 
 def test_bad_arguments_of_the_next_steps_are_rejected_on_the_host(lib):
