@@ -217,6 +217,20 @@ ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dt
                             int N, int Hq, int Hkv, int k, int d, float scale, float *O,
                             void *workspace, size_t workspace_bytes, ws_stream stream);
 
+/*
+ * Gather and attend in one pass (Sec. 3.3: the synapse holds the landmark rows only; Sec. 4: O(k) per query): the
+ * same attention read straight from the chosen rows of the cache, for callers that do not need the synapse as a
+ * buffer of its own,
+ *     O[n,q,:] = softmax_t( scale * Q[n,q,:] . K[q/g, idx[q/g,t], :] ) . V[q/g, idx[q/g,:], :],   t < k.
+ * The result is bit-identical to ws_synapse_gather followed by ws_synapse_attend.
+ *   Q dev [N,Hq,d];  K, V dev [Hkv,L,d];  idx dev [Hkv,k], an index outside [0,L) is clamped into range;
+ *   O dev [N,Hq,d] fp32, written;  workspace as for ws_synapse_attend (same size, WS_OP_ATTEND).
+ *   L * d * sizeof(element) must stay below 2^32 (WS_ERR_UNSUPPORTED otherwise).
+ */
+ws_status ws_synapse_attend_indexed(const void *Q, const void *K, const void *V, const int32_t *idx,
+                                    ws_dtype dt, int N, int Hq, int Hkv, int L, int k, int d, float scale,
+                                    float *O, void *workspace, size_t workspace_bytes, ws_stream stream);
+
 /* ------------------------------------------------------------------------------------------
  * Steps next to the hot path.
  * ------------------------------------------------------------------------------------------ */

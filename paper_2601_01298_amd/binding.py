@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.ws_synapse_gather.restype = ci
         L.ws_synapse_attend.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
         L.ws_synapse_attend.restype = ci
+        L.ws_synapse_attend_indexed.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
+        L.ws_synapse_attend_indexed.restype = ci
         L.ws_synapse_attention_mass.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, vp, sz, vp]
         L.ws_synapse_attention_mass.restype = ci
         L.ws_synapse_density_append.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.POINTER(cf), vp, vp, vp, sz, vp]
@@ -307,6 +309,35 @@ def ws_synapse_attend(Q: torch.Tensor, Ks: torch.Tensor, Vs: torch.Tensor, scale
     wptr, wlen = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
     _check(lib().ws_synapse_attend(Q.data_ptr(), Ks.data_ptr(), Vs.data_ptr(), dt, N, Hq, Hkv, k, d, float(scale),
                                    O.data_ptr(), wptr, wlen, _stream(stream)), "ws_synapse_attend")
+    return O
+
+
+def ws_synapse_attend_indexed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx: torch.Tensor, scale: float = 0.0,
+                              O: torch.Tensor | None = None, workspace=None, stream=None):
+    """Q [N,Hq,d], K,V [Hkv,L,d], idx [Hkv,k] int32 -> O [N,Hq,d] fp32: gather and attend in one pass."""
+    _dev(Q, "Q")
+    _dev(K, "K")
+    if Q.dim() != 3 or K.dim() != 3 or idx.dim() != 2:
+        raise ValueError("Q must be [N,Hq,d], K [Hkv,L,d] and idx [Hkv,k]")
+    N, Hq, d = Q.shape
+    Hkv, L, dk = K.shape
+    k = idx.shape[1]
+    dt = _dtype_code(Q)
+    if dk != d:
+        raise ValueError(f"Q has head dimension {d}, K {dk}")
+    _want(K, "K", (Hkv, L, d), Q.dtype)
+    _want(V, "V", (Hkv, L, d), Q.dtype)
+    _want(idx, "idx", (Hkv, k), torch.int32)
+    if O is None:
+        O = _new((N, Hq, d), torch.float32, Q.device, stream)
+    _want(O, "O", (N, Hq, d), torch.float32)
+    need = ws_synapse_workspace_bytes(WS_OP_ATTEND, dt, Hkv, k, d, k, N, Hq)
+    if need or workspace is not None:
+        workspace = _workspace(need, Q.device, workspace, stream)
+    wptr, wlen = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(lib().ws_synapse_attend_indexed(Q.data_ptr(), K.data_ptr(), V.data_ptr(), idx.data_ptr(), dt, N, Hq, Hkv, L,
+                                           k, d, float(scale), O.data_ptr(), wptr, wlen, _stream(stream)),
+           "ws_synapse_attend_indexed")
     return O
 
 

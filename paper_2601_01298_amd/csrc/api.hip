@@ -223,6 +223,27 @@ ws_status ws_synapse_attend(const void *Q, const void *Ks, const void *Vs, ws_dt
     return e == hipSuccess ? WS_OK : WS_ERR_HIP;
 }
 
+ws_status ws_synapse_attend_indexed(const void *Q, const void *K, const void *V, const int32_t *idx, ws_dtype dt, int N,
+                                    int Hq, int Hkv, int L, int k, int d, float scale, float *O, void *workspace,
+                                    size_t workspace_bytes, ws_stream stream)
+{
+    ws_status s = check_common(dt, d);
+    if (s != WS_OK) return s;
+    if (!Q || !K || !V || !idx || !O || N < 1 || Hq < 1 || Hkv < 1 || L < 1 || k < 1) return WS_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0) return WS_ERR_INVALID_ARG;
+    if (Hkv > 65535) return WS_ERR_UNSUPPORTED;
+    if ((unsigned long long)L * d * (dt == WS_BF16 ? 2 : 4) >= (1ull << 32)) return WS_ERR_UNSUPPORTED;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(idx, 4))
+        return WS_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return WS_ERR_INVALID_ARG;
+    if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)d);
+    s = check_ws(workspace, workspace_bytes, ws::attend_workspace_bytes(dt == WS_BF16, N, Hq, Hkv, k, d));
+    if (s != WS_OK) return s;
+    const hipError_t e = ws::launch_attend_indexed(Q, K, V, idx, dt == WS_BF16, N, Hq, Hkv, L, k, d, scale, O, workspace,
+                                                   (hipStream_t)stream);
+    return e == hipSuccess ? WS_OK : WS_ERR_HIP;
+}
+
 ws_status ws_synapse_attention_mass(const void *K, const void *Q, ws_dtype dt, int G, int Hkv, int Hq, int L, int d,
                                     float scale, int as_density, float *out, void *workspace, size_t workspace_bytes,
                                     ws_stream stream)

@@ -19,6 +19,10 @@
 // of an "even dimensions" and an "odd dimensions" tile.
 //
 // fp32 path (small configurations): one wave per (agent, query head), plain fp32 FMAs.
+//
+// Both paths also exist in an indexed form that reads the chosen rows K[h, idx[h,t], :] straight from the
+// cache (Sec. 3.3: the synapse holds the landmark rows only), so a caller that does not need the synapse as a
+// buffer of its own skips the gather pass: same arithmetic in the same order, bit-identical output.
 #include "ws_internal.h"
 
 namespace ws {
@@ -59,6 +63,12 @@ __device__ __forceinline__ void dma16(const void *base /* wave-uniform */, unsig
         __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const void *)lds_base);
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_offset), "s"(base), "s"(la) : "memory", "m0");
 }
+// A 32-bit load the compiler keeps no count for (its own wait would also cover every copy in flight); the
+// caller waits with wait_vmcnt and pins the first use behind that wait.
+__device__ __forceinline__ void load_u32_uncounted(uint32_t &dst, const void *base /* wave-uniform */, unsigned byte_offset)
+{
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(byte_offset), "s"(base) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -88,11 +98,17 @@ __device__ __forceinline__ void wait_vmcnt()
 //     accumulator is rescaled a few times per query instead of once per tile (weights stay below
 //     2^8, harmless in fp32 and in the bf16 hi+lo split);
 //   - packed conversions (v_cvt_pk_bf16_f32) and byte permutes (v_perm_b32) build the MFMA operands.
-template <int D>
+//
+// IDX: Ks / Vs are the whole cache [Hkv, L, D] and landmark t of head h is row idx[h, t] (clamped into [0, L)).
+// A thread then needs the index of each row it copies one step before the copy is issued: the indices of a stage
+// are asked for one stage earlier than its copies (into a ring of register sets, one per stage buffer), so the copy
+// never waits for the youngest load in flight.  Order of a thread's memory operations, PF = 2:
+//     idx(0) idx(1) Q | copies(0) idx(2) copies(1) | idx(3) copies(2) | idx(4) copies(3) | ...
+template <int D, bool IDX>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
 attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, const uint16_t *__restrict__ Vs,
             float *__restrict__ O, int N, int Hq, int Hkv, int k, float scale_log2, int parts, int splits,
-            float *__restrict__ partial)
+            float *__restrict__ partial, const int32_t *__restrict__ idx, int L)
 {
     constexpr int NK = D / 16;   // k-steps of the score product
     constexpr int NP = D / 64;   // 64-wide spans of head dimensions, each an even and an odd tile
@@ -102,6 +118,7 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     constexpr int NBUF = D == 64 ? 3 : 2;      // stage buffers (a stage: K and V tile of both halves)
     constexpr int PF = NBUF - 1;               // stages in flight ahead of the one being read
     constexpr int NC = 4 * NLD;                // copies per thread and stage
+    constexpr int NI = IDX ? 2 * NLD : 0;      // index loads per thread and stage
     constexpr int NO = 2 * NP * 16;
     constexpr int STG = 4 * TP;                // pieces per stage: [half][K tile, V tile]
     constexpr int XCH = 2 * (NO + 2) * 64 * 4 / 16;                  // the merge area, in 16-byte units
@@ -124,8 +141,8 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // the same for every lane: what follows from it is scalar
     const int lane = tid & 63, nq = lane & 31, hb = lane >> 5;
-    const uint16_t *Kh = Ks + (size_t)h * k * D;
-    const uint16_t *Vh = Vs + (size_t)h * k * D;
+    const uint16_t *Kh = Ks + (size_t)h * (IDX ? L : k) * D;
+    const uint16_t *Vh = Vs + (size_t)h * (IDX ? L : k) * D;
     const int wt = wave & 1, half = wave >> 1;
     const int tile = part * 2 + wt;
     const bool tile_live = tile * 32 < M;    // wave-uniform
@@ -157,12 +174,34 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     const unsigned last = (unsigned)(k - 1) * RB;
     unsigned off0 = (unsigned)(T0 * 32 + crow) * RB;                 // this thread's first row of the next stage, half 0 ...
     unsigned off1 = (unsigned)((T0 + tA) * 32 + crow) * RB;          // ... and half 1 (may lie past the end: clamped, never read)
+    // indexed form: ring of index register sets; set s holds the rows of the stage that goes to buffer s
+    uint32_t ring[NBUF][IDX ? 2 * NLD : 1];
+    const int32_t *idxh = idx + (IDX ? (size_t)h * k : 0);
+    int pos0 = T0 * 32 + crow, pos1 = (T0 + tA) * 32 + crow;         // landmark positions of the next index loads
+    auto ask = [&](int bi) {                                         // indices of the next stage not asked for yet
+        if constexpr (IDX) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                load_u32_uncounted(ring[bi][2 * i], idxh, 4u * (unsigned)min(pos0 + i * (256 / CH), k - 1));
+                load_u32_uncounted(ring[bi][2 * i + 1], idxh, 4u * (unsigned)min(pos1 + i * (256 / CH), k - 1));
+            }
+            pos0 += 32;
+            pos1 += 32;
+        }
+    };
     auto issue = [&](int bi) {                                       // bi: stage buffer, a compile-time constant at every call
         uint4 *buf = smem + bi * STG + wave * 64;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const unsigned r0 = min(off0 + (unsigned)(i * (256 / CH)) * RB, last);
-            const unsigned r1 = min(off1 + (unsigned)(i * (256 / CH)) * RB, last);
+            unsigned r0, r1;
+            if constexpr (IDX) {                                     // (the caller has waited for this set)
+                asm volatile("" : "+v"(ring[bi][2 * i]), "+v"(ring[bi][2 * i + 1]));
+                r0 = (unsigned)min(max((int)ring[bi][2 * i], 0), L - 1) * RB;
+                r1 = (unsigned)min(max((int)ring[bi][2 * i + 1], 0), L - 1) * RB;
+            } else {
+                r0 = min(off0 + (unsigned)(i * (256 / CH)) * RB, last);
+                r1 = min(off1 + (unsigned)(i * (256 / CH)) * RB, last);
+            }
             dma16(Kh, r0 + kpiece, buf + 0 * TP + 256 * i);
             dma16(Vh, r0 + vpiece, buf + 1 * TP + 256 * i);
             dma16(Kh, r1 + kpiece, buf + 2 * TP + 256 * i);
@@ -179,14 +218,28 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     // stay in flight, and the empty statement behind it pins the operands' first use after that wait.
     const uint16_t *qrow = Q + ((size_t)agent * Hq + qh) * D + hb * 8;
     u32x4_t qw[NK];
+    if constexpr (IDX) {
+        ask(0);
+        ask(1);
+    }
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk)
         asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qw[kk]) : "v"(qrow), "n"(kk * 32) : "memory");
+    if constexpr (IDX) {
+        wait_vmcnt<0>();                       // the first two stages' indices (and the queries) are in
 #pragma unroll
-    for (int p = 0; p < PF; ++p)
-        if (p < tA) issue(p);
-    if (tA >= PF) wait_vmcnt<PF * NC>();
-    else wait_vmcnt<0>();
+        for (int p = 0; p < PF; ++p) {
+            if (p < tA) issue(p);
+            if (p + 2 <= PF) ask(p + 2);
+        }
+        // from here on every stage asks for one set of indices and issues one set of copies, in that order
+    } else {
+#pragma unroll
+        for (int p = 0; p < PF; ++p)
+            if (p < tA) issue(p);
+        if (tA >= PF) wait_vmcnt<PF * NC>();
+        else wait_vmcnt<0>();
+    }
     bf16x8_t qf[NK];
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) {
@@ -202,11 +255,18 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     // One stage: `bi` is its buffer (a constant at every call, so LDS offsets are immediates)
     auto stage = [&](int sidx, int bi) {
         // this wave's copies of the stage have landed (those of later stages may still be in flight) ...
-        if (PF == 2 && sidx + 1 < tA) wait_vmcnt<NC>();
+        // (younger than them: the next stage's copies and, indexed, the index loads behind which they were issued)
+        if (PF == 2 && sidx + 1 < tA) wait_vmcnt<NC + NI>();
         else wait_vmcnt<0>();
         // ... and so have everybody's; all waves are through with the buffer that is refilled next
         lds_only_barrier();
-        if (sidx + PF < tA) issue((bi + PF) % NBUF);
+        if constexpr (IDX) ask(bi);            // rows of stage sidx + PF + 1; its set last served stage sidx
+        if (sidx + PF < tA) {
+            // indexed: the set of stage sidx + PF, asked for one stage ago, has only the previous stage's copies and
+            // the loads just issued behind it
+            if constexpr (IDX) wait_vmcnt<NC + NI>();
+            issue((bi + PF) % NBUF);
+        }
         const int t = T0 + (half ? tA + sidx : sidx);
         if (!tile_live || t >= nT) return;             // wave-uniform
         const int t0 = t * 32;
@@ -388,21 +448,22 @@ attend_merge(const float *__restrict__ partial, float *__restrict__ O, long long
     *reinterpret_cast<float4 *>(O + row * D + 4 * c) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
-template <int D>
+template <int D, bool IDX>
 __global__ void __launch_bounds__(64)
 attend_f32(const float *__restrict__ Q, const float *__restrict__ Ks, const float *__restrict__ Vs,
-           float *__restrict__ O, int Hq, int Hkv, int k, float scale)
+           float *__restrict__ O, int Hq, int Hkv, int k, float scale, const int32_t *__restrict__ idx, int L)
 {
     constexpr int NC = D / 64;   // output dims per lane
     __shared__ float ps[64];
+    __shared__ int rs[64];       // cache row of each landmark of the chunk
     __shared__ float qs[D];
     const int lane = threadIdx.x;
     const int nq = blockIdx.x;             // agent * Hq + query head
     const int q = nq % Hq;
     const int h = q / (Hq / Hkv);
     const float *qrow = Q + (size_t)nq * D;
-    const float *Kh = Ks + (size_t)h * k * D;
-    const float *Vh = Vs + (size_t)h * k * D;
+    const float *Kh = Ks + (size_t)h * (IDX ? L : k) * D;
+    const float *Vh = Vs + (size_t)h * (IDX ? L : k) * D;
 #pragma unroll
     for (int c = 0; c < NC; ++c) qs[lane + 64 * c] = qrow[lane + 64 * c];
     __syncthreads();
@@ -415,8 +476,10 @@ attend_f32(const float *__restrict__ Q, const float *__restrict__ Ks, const floa
     for (int c0 = 0; c0 < k; c0 += 64) {
         const int t = c0 + lane;
         float z = -__builtin_inff();
+        int row = t;
+        if (IDX && t < k) row = min(max(idx[(size_t)h * k + t], 0), L - 1);
         if (t < k) {
-            const float *kr = Kh + (size_t)t * D;
+            const float *kr = Kh + (size_t)row * D;
             float s = 0.0f;
 #pragma unroll 8
             for (int c = 0; c < D; ++c) s = fmaf(qs[c], kr[c], s);
@@ -431,6 +494,7 @@ attend_f32(const float *__restrict__ Q, const float *__restrict__ Ks, const floa
         const float p = (t < k) ? expf(z - mnew) : 0.0f;
         __syncthreads();                   // previous chunk's readers are done with ps
         ps[lane] = p;
+        rs[lane] = row;
         float psum = p;
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) psum += __shfl_xor(psum, o);
@@ -440,7 +504,7 @@ attend_f32(const float *__restrict__ Q, const float *__restrict__ Ks, const floa
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             float acc = oacc[c] * corr;
-            for (int j = 0; j < cnt; ++j) acc = fmaf(ps[j], Vh[(size_t)(c0 + j) * D + lane + 64 * c], acc);
+            for (int j = 0; j < cnt; ++j) acc = fmaf(ps[j], Vh[(size_t)rs[j] * D + lane + 64 * c], acc);
             oacc[c] = acc;
         }
     }
@@ -471,8 +535,9 @@ size_t attend_workspace_bytes(bool bf16, int N, int Hq, int Hkv, int k, int d)
     return s == 1 ? 0 : round_up((size_t)s * N * Hq * (d + 4) * sizeof(float), 256);
 }
 
-hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq, int Hkv, int k,
-                         int d, float scale, float *O, void *ws, hipStream_t st)
+template <bool IDX>
+static hipError_t launch_attend_any(const void *Q, const void *Ks, const void *Vs, const int32_t *idx, int L, bool bf16,
+                                    int N, int Hq, int Hkv, int k, int d, float scale, float *O, void *ws, hipStream_t st)
 {
     if (bf16) {
         const int g = Hq / Hkv;
@@ -489,14 +554,14 @@ hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf1
         float *part = reinterpret_cast<float *>(ws);
         const long long rows = (long long)N * Hq;
         if (d == 64) {
-            hipLaunchKernelGGL(attend_bf16<64>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts, splits,
-                               part);
+            hipLaunchKernelGGL((attend_bf16<64, IDX>), grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts,
+                               splits, part, idx, L);
             if (splits > 1)
                 hipLaunchKernelGGL(attend_merge<64>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, part, O, rows,
                                    splits);
         } else if (d == 128) {
-            hipLaunchKernelGGL(attend_bf16<128>, grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts, splits,
-                               part);
+            hipLaunchKernelGGL((attend_bf16<128, IDX>), grid, dim3(256), 0, st, q, ks, vs, O, N, Hq, Hkv, k, sl2, (int)parts,
+                               splits, part, idx, L);
             if (splits > 1)
                 hipLaunchKernelGGL(attend_merge<128>, dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, st, part, O, rows,
                                    splits);
@@ -510,13 +575,27 @@ hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf1
         const float *ks = reinterpret_cast<const float *>(Ks);
         const float *vs = reinterpret_cast<const float *>(Vs);
         if (d == 64)
-            hipLaunchKernelGGL(attend_f32<64>, dim3((unsigned)blocks), dim3(64), 0, st, q, ks, vs, O, Hq, Hkv, k, scale);
+            hipLaunchKernelGGL((attend_f32<64, IDX>), dim3((unsigned)blocks), dim3(64), 0, st, q, ks, vs, O, Hq, Hkv, k, scale,
+                               idx, L);
         else if (d == 128)
-            hipLaunchKernelGGL(attend_f32<128>, dim3((unsigned)blocks), dim3(64), 0, st, q, ks, vs, O, Hq, Hkv, k, scale);
+            hipLaunchKernelGGL((attend_f32<128, IDX>), dim3((unsigned)blocks), dim3(64), 0, st, q, ks, vs, O, Hq, Hkv, k, scale,
+                               idx, L);
         else
             return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq, int Hkv, int k,
+                         int d, float scale, float *O, void *ws, hipStream_t st)
+{
+    return launch_attend_any<false>(Q, Ks, Vs, nullptr, 0, bf16, N, Hq, Hkv, k, d, scale, O, ws, st);
+}
+
+hipError_t launch_attend_indexed(const void *Q, const void *K, const void *V, const int32_t *idx, bool bf16, int N,
+                                 int Hq, int Hkv, int L, int k, int d, float scale, float *O, void *ws, hipStream_t st)
+{
+    return launch_attend_any<true>(Q, K, V, idx, L, bf16, N, Hq, Hkv, k, d, scale, O, ws, st);
 }
 
 }  // namespace ws

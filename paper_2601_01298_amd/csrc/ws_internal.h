@@ -110,6 +110,9 @@ hipError_t launch_gather(const void *K, const void *V, int row_bytes, int H, int
 size_t attend_workspace_bytes(bool bf16, int N, int Hq, int Hkv, int k, int d);
 hipError_t launch_attend(const void *Q, const void *Ks, const void *Vs, bool bf16, int N, int Hq,
                          int Hkv, int k, int d, float scale, float *O, void *ws, hipStream_t st);
+// the same over rows idx[h,t] of the whole cache K, V [Hkv, L, d] (same workspace, bit-identical result)
+hipError_t launch_attend_indexed(const void *Q, const void *K, const void *V, const int32_t *idx, bool bf16, int N,
+                                 int Hq, int Hkv, int L, int k, int d, float scale, float *O, void *ws, hipStream_t st);
 
 // ---- steps next to the hot path -------------------------------------------------------
 bool mass_supported(int Hkv, int Hq);

@@ -75,6 +75,11 @@ int main(void)
     CHECK(ws_synapse_attend(fake, fake, fake, WS_BF16, 100, 70000, 70000, 20, 64, 0.0f, fake, NULL, 0, NULL) == WS_ERR_UNSUPPORTED);
     CHECK(ws_synapse_attend(fake, fake, fake, WS_BF16, 256, 32, 8, 2621, 128, 0.0f, fake, NULL, 0, NULL) == WS_ERR_WORKSPACE);
     CHECK(ws_synapse_attend(fake, fake, fake, WS_BF16, 256, 32, 8, 2621, 128, 0.0f, fake, fake, big, NULL) == WS_OK);
+    CHECK(ws_synapse_attend_indexed(fake, fake, fake, fake, WS_BF16, 100, 12, 3, 4096, 20, 64, 0.0f, fake, NULL, 0, NULL) == WS_OK);
+    CHECK(ws_synapse_attend_indexed(fake, fake, fake, NULL, WS_BF16, 100, 12, 3, 4096, 20, 64, 0.0f, fake, NULL, 0, NULL) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_attend_indexed(fake, fake, fake, fake, WS_BF16, 100, 12, 3, 0, 20, 64, 0.0f, fake, NULL, 0, NULL) == WS_ERR_INVALID_ARG);
+    CHECK(ws_synapse_attend_indexed(fake, fake, fake, fake, WS_F32, 100, 12, 3, 1 << 23, 20, 128, 0.0f, fake, NULL, 0, NULL) == WS_ERR_UNSUPPORTED);
+    CHECK(ws_synapse_attend_indexed(fake, fake, fake, fake, WS_BF16, 256, 32, 8, 131072, 2621, 128, 0.0f, fake, NULL, 0, NULL) == WS_ERR_WORKSPACE);
 
     CHECK(ws_synapse_attention_mass(fake, fake, WS_BF16, 2, 4, 8, 1000, 64, 0.0f, 1, fake, fake, big, NULL) == WS_OK);
     CHECK(ws_synapse_attention_mass(fake, fake, WS_BF16, 2, 4, 6, 1000, 64, 0.0f, 1, fake, fake, big, NULL) == WS_ERR_INVALID_ARG);
@@ -106,7 +111,7 @@ int main(void)
     CHECK(ws_synapse_workspace_bytes(WS_OP_DENSITY, WS_BF16, 0, 1000, 64, 1, 1, 1) == (size_t)-1);
     for (int s = 0; s <= 8; ++s) CHECK(ws_status_string((ws_status)s) != NULL);
     CHECK(ws_synapse_select_is_resident(WS_BF16, H, 1000, 64) == 1);
-    CHECK(g_launches - before == 10);
+    CHECK(g_launches - before == 11);
 
     free(sigma);
     printf(failures ? "%d check(s) failed\n" : "all checks passed\n", failures);

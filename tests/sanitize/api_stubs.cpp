@@ -49,6 +49,12 @@ hipError_t launch_attend(const void *, const void *, const void *, bool, int, in
     ++g_launches;
     return hipSuccess;
 }
+hipError_t launch_attend_indexed(const void *, const void *, const void *, const int32_t *, bool, int, int, int, int, int,
+                                 int, float, float *, void *, hipStream_t)
+{
+    ++g_launches;
+    return hipSuccess;
+}
 bool mass_supported(int Hkv, int Hq) { return Hq <= 128 && Hq / Hkv <= 8; }
 size_t mass_workspace_bytes(int, int Hq, int L) { return (size_t)Hq * L * 4; }
 hipError_t launch_attention_mass(const void *, const void *, bool, int, int, int, int, int, float, int, float *, void *,

@@ -124,6 +124,12 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert A(fake, fake, fake, b.WS_BF16, 4, 4, 4, 10, 64, float("inf"), fake, None, 0, None) == b.WS_ERR_INVALID_ARG
     assert A(fake, fake, None, b.WS_BF16, 4, 4, 4, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
     assert A(fake, fake, fake, b.WS_BF16, 256, 32, 8, 2621, 128, 0.0, fake, None, 0, None) == b.WS_ERR_WORKSPACE   # split range
+    AI = lib.ws_synapse_attend_indexed
+    assert AI(fake, fake, fake, None, b.WS_BF16, 4, 4, 4, 100, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
+    assert AI(fake, fake, fake, fake, b.WS_BF16, 4, 6, 4, 100, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG   # 6 % 4
+    assert AI(fake, fake, fake, fake, b.WS_BF16, 4, 4, 4, 0, 10, 64, 0.0, fake, None, 0, None) == b.WS_ERR_INVALID_ARG
+    assert AI(fake, fake, fake, fake, b.WS_F32, 4, 4, 4, 1 << 23, 10, 128, 0.0, fake, None, 0, None) == b.WS_ERR_UNSUPPORTED
+    assert AI(fake, fake, fake, fake, b.WS_BF16, 256, 32, 8, 131072, 2621, 128, 0.0, fake, None, 0, None) == b.WS_ERR_WORKSPACE
 
 
 def test_bad_arguments_of_the_next_steps_are_rejected_on_the_host(lib):

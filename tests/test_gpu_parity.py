@@ -431,6 +431,40 @@ def test_attend_matches_oracle(ws, oracle, dtype, N, Hq, Hkv, k, d):
     assert attn_rel_err(O2, oracle.attend(Q, Ks, Vs, scale=0.05)) <= ATT_TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype,N,Hq,Hkv,L,k,d", [
+    ("bf16", 100, 16, 16, 4096, 82, 64),      # several heads per die group, ragged last tile
+    ("bf16", 7, 8, 2, 300, 33, 64),           # grouped queries, one more landmark than a tile
+    ("bf16", 33, 4, 4, 50, 1, 64),            # a single landmark
+    ("bf16", 50, 8, 2, 1000, 164, 128),       # d = 128: one stage ahead, two rows per thread and half
+    ("bf16", 256, 4, 1, 20000, 655, 64),      # few heads, many landmarks: 21 stages
+    ("bf16", 64, 8, 2, 9000, 2621, 128),      # landmark range split over workgroups, merged from the workspace
+    ("bf16", 40, 4, 4, 64, 64, 64),           # k = L: every row, in pick order
+    ("f32", 4, 1, 1, 100, 10, 64), ("f32", 5, 6, 3, 500, 130, 128),
+])
+def test_attend_indexed_is_gather_then_attend(ws, oracle, dtype, N, Hq, Hkv, L, k, d):
+    """Reading the chosen rows straight from the cache gives, bit for bit, what gather + attend give, and both
+    match the oracle's attention over the oracle's gathered rows."""
+    import torch
+    rng = np.random.default_rng(23)
+    def draw(*shape):
+        x = rng.standard_normal(shape).astype(np.float32)
+        return syn.round_to_bf16(x) if dtype == "bf16" else x
+    Q, K, V = draw(N, Hq, d), 2.0 * draw(Hkv, L, d), draw(Hkv, L, d)
+    idx = np.stack([rng.permutation(L)[:k] for _ in range(Hkv)]).astype(np.int32)
+    Qd, Kd, Vd, idxd = to_device(Q, dtype), to_device(K, dtype), to_device(V, dtype), torch.from_numpy(idx).cuda()
+    O1 = ws.ws_synapse_attend_indexed(Qd, Kd, Vd, idxd)
+    Ks, Vs = ws.ws_synapse_gather(Kd, Vd, idxd)
+    O2 = ws.ws_synapse_attend(Qd, Ks, Vs)
+    assert torch.equal(O1.view(torch.int32), O2.view(torch.int32))
+    Ks_ref = np.stack([oracle.gather(K[h], V[h], idx[h])[0] for h in range(Hkv)])
+    Vs_ref = np.stack([oracle.gather(K[h], V[h], idx[h])[1] for h in range(Hkv)])
+    err = attn_rel_err(O1.cpu().numpy(), oracle.attend(Q, Ks_ref, Vs_ref))
+    print(f"{dtype} N={N} Hq={Hq} Hkv={Hkv} L={L} k={k} d={d}: rel err {err:.2e}")
+    assert err <= ATT_TOL[dtype]
+    O3 = ws.ws_synapse_attend_indexed(Qd, Kd, Vd, idxd, scale=0.05)
+    assert torch.equal(O3.view(torch.int32), ws.ws_synapse_attend(Qd, Ks, Vs, scale=0.05).view(torch.int32))
+
+
 # ------------------------------------------------------------------------- whole chain
 @pytest.mark.parametrize("cfg", [1, 2])
 def test_chain_small_configs(ws, oracle, cfg):
