@@ -14,9 +14,9 @@
 // is free, as long as Vs^T is fetched in the same order), so P never goes through LDS.  P enters
 // that MFMA as a bf16 hi part plus a bf16 lo part (two instructions), which keeps 16 significant
 // bits of every weight; the denominator sums the unrounded fp32 weights.
-// Vs^T is built without a transpose pass: a lane fetches the 32-bit word holding head
-// dimensions (2n, 2n+1) from 8 landmark rows and splits low and high halves into the operand
-// of an "even dimensions" and an "odd dimensions" tile.
+// Vs^T needs no transpose pass and no vector instruction: the LDS transpose read
+// (ds_read_b64_tr_b16) hands a lane the values of ONE head dimension from four consecutive
+// landmark rows, which is the operand layout of the second MFMA.
 //
 // fp32 path (small configurations): one wave per (agent, query head), plain fp32 FMAs.
 //
@@ -28,6 +28,7 @@
 namespace ws {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
@@ -89,7 +90,7 @@ __device__ __forceinline__ void wait_vmcnt()
 // query tile), a wave has PF stages of memory latency covered at no cost in registers, and the
 // operands arrive by LDS reads with constant offsets.  K tiles are stored with their 16-byte pieces
 // XOR-swizzled by row (applied on the global side of the copy) so that the MFMA operand reads, one
-// row per lane, spread over the banks; V tiles are stored as they are (their reads run along a row).
+// row per lane, spread over the banks; V tiles likewise, by the rule their transpose reads need (see read_v).
 // One LDS-only barrier per stage publishes the stage and retires the buffer that is refilled next.
 //
 // The per-tile instruction count is what is optimised in the softmax:
@@ -97,7 +98,7 @@ __device__ __forceinline__ void wait_vmcnt()
 //   - the running maximum is only moved when a tile exceeds it by more than 2^8, so the
 //     accumulator is rescaled a few times per query instead of once per tile (weights stay below
 //     2^8, harmless in fp32 and in the bf16 hi+lo split);
-//   - packed conversions (v_cvt_pk_bf16_f32) and byte permutes (v_perm_b32) build the MFMA operands.
+//   - packed conversions (v_cvt_pk_bf16_f32) build the weights' operand, the V operand comes ready from the LDS.
 //
 // IDX: Ks / Vs are the whole cache [Hkv, L, D] and landmark t of head h is row idx[h, t] (clamped into [0, L)).
 // A thread then needs the index of each row it copies one step before the copy is issued: the indices of a stage
@@ -105,7 +106,7 @@ __device__ __forceinline__ void wait_vmcnt()
 // never waits for the youngest load in flight.  Order of a thread's memory operations, PF = 2:
 //     idx(0) idx(1) Q | copies(0) idx(2) copies(1) | idx(3) copies(2) | idx(4) copies(3) | ...
 template <int D, bool IDX>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2)))
 attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, const uint16_t *__restrict__ Vs,
             float *__restrict__ O, int N, int Hq, int Hkv, int k, float scale_log2, int parts, int splits,
             float *__restrict__ partial, const int32_t *__restrict__ idx, int L)
@@ -170,37 +171,43 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     constexpr unsigned RB = D * 2;                                   // bytes per landmark row
     const int crow = tid / CH;
     const unsigned kpiece = (unsigned)(((tid % CH) ^ (crow & 7)) * 16);
-    const unsigned vpiece = (unsigned)((tid % CH) * 16);
+    // V: slot c of row r holds piece c ^ vswz(r), vswz(r) = 4 ((r >> 1) & 1) at d = 64, 4 (r & 3) at d = 128 (a function
+    // of r & 7, so it is the same for every row a thread copies)
+    const unsigned vpiece = (unsigned)(((tid % CH) ^ (D == 64 ? ((crow >> 1) & 1) << 2 : (crow & 3) << 2)) * 16);
     const unsigned last = (unsigned)(k - 1) * RB;
-    unsigned off0 = (unsigned)(T0 * 32 + crow) * RB;                 // this thread's first row of the next stage, half 0 ...
-    unsigned off1 = (unsigned)((T0 + tA) * 32 + crow) * RB;          // ... and half 1 (may lie past the end: clamped, never read)
+    unsigned off0 = (unsigned)(T0 * 32 + crow) * RB;                 // this thread's first V row of the next stage, half 0;
+    const unsigned hoff = (unsigned)(tA * 32) * RB;                  // half 1 lies this much further on (uniform; past the end: clamped, never read)
     // indexed form: ring of index register sets; set s holds the rows of the stage that goes to buffer s
+    // (half 0, half 1 per copy pass)
     uint32_t ring[NBUF][IDX ? 2 * NLD : 1];
     const int32_t *idxh = idx + (IDX ? (size_t)h * k : 0);
-    int pos0 = T0 * 32 + crow, pos1 = (T0 + tA) * 32 + crow;         // landmark positions of the next index loads
+    int pos0 = T0 * 32 + crow;                                       // landmark position of the next index loads, half 0
     auto ask = [&](int bi) {                                         // indices of the next stage not asked for yet
         if constexpr (IDX) {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
-                load_u32_uncounted(ring[bi][2 * i], idxh, 4u * (unsigned)min(pos0 + i * (256 / CH), k - 1));
-                load_u32_uncounted(ring[bi][2 * i + 1], idxh, 4u * (unsigned)min(pos1 + i * (256 / CH), k - 1));
+                const int a0 = pos0 + i * (256 / CH), a1 = a0 + tA * 32;
+                load_u32_uncounted(ring[bi][2 * i + 0], idxh, 4u * (unsigned)min(a0, k - 1));
+                load_u32_uncounted(ring[bi][2 * i + 1], idxh, 4u * (unsigned)min(a1, k - 1));
             }
             pos0 += 32;
-            pos1 += 32;
         }
+    };
+    auto row_of = [&](uint32_t &reg) {                               // (the caller has waited for this register's load)
+        asm volatile("" : "+v"(reg));
+        return (unsigned)min(max((int)reg, 0), L - 1) * RB;
     };
     auto issue = [&](int bi) {                                       // bi: stage buffer, a compile-time constant at every call
         uint4 *buf = smem + bi * STG + wave * 64;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             unsigned r0, r1;
-            if constexpr (IDX) {                                     // (the caller has waited for this set)
-                asm volatile("" : "+v"(ring[bi][2 * i]), "+v"(ring[bi][2 * i + 1]));
-                r0 = (unsigned)min(max((int)ring[bi][2 * i], 0), L - 1) * RB;
-                r1 = (unsigned)min(max((int)ring[bi][2 * i + 1], 0), L - 1) * RB;
+            if constexpr (IDX) {
+                r0 = row_of(ring[bi][2 * i + 0]);
+                r1 = row_of(ring[bi][2 * i + 1]);
             } else {
                 r0 = min(off0 + (unsigned)(i * (256 / CH)) * RB, last);
-                r1 = min(off1 + (unsigned)(i * (256 / CH)) * RB, last);
+                r1 = min(off0 + hoff + (unsigned)(i * (256 / CH)) * RB, last);
             }
             dma16(Kh, r0 + kpiece, buf + 0 * TP + 256 * i);
             dma16(Vh, r0 + vpiece, buf + 1 * TP + 256 * i);
@@ -208,9 +215,7 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
             dma16(Vh, r1 + vpiece, buf + 3 * TP + 256 * i);
         }
         off0 += 32 * RB;
-        off1 += 32 * RB;
     };
-
     // The query rows are asked for first and the first stages' copies right behind them: every workgroup starts at the
     // same moment, so what is asked for first arrives first, and the first tile needs the queries and stage 0 only.
     // The query loads are written as assembly so that the compiler keeps no count for them (its wait at their first use,
@@ -225,21 +230,15 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk)
         asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qw[kk]) : "v"(qrow), "n"(kk * 32) : "memory");
-    if constexpr (IDX) {
-        wait_vmcnt<0>();                       // the first two stages' indices (and the queries) are in
+    if constexpr (IDX) wait_vmcnt<0>();        // the first two stages' indices (and the queries) are in
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            if (p < tA) issue(p);
-            if (p + 2 <= PF) ask(p + 2);
-        }
-        // from here on every stage asks for one set of indices and issues one set of copies, in that order
-    } else {
-#pragma unroll
-        for (int p = 0; p < PF; ++p)
-            if (p < tA) issue(p);
-        if (tA >= PF) wait_vmcnt<PF * NC>();
-        else wait_vmcnt<0>();
+    for (int p = 0; p < PF; ++p) {
+        if (p < tA) issue(p);
+        if (IDX && p + 2 <= PF) ask(p + 2);
     }
+    // (indexed: from here on every stage asks for one set of indices and issues one set of copies, in that order)
+    if (tA >= PF) wait_vmcnt<PF * NC + (PF - 1) * NI>();             // the queries are in, the stages may be in flight
+    else wait_vmcnt<0>();
     bf16x8_t qf[NK];
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) {
@@ -247,10 +246,129 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
         qf[kk] = __builtin_bit_cast(bf16x8_t, qw[kk]);
     }
 
-    // LDS read positions of this lane: K row nq of the tile (its swizzled pieces), V words of head dimensions 2nq, 2nq+1
-    int kslot[NK];
+    // ---- the tile loop: scores, softmax weights and P.V of a tile one after the other.  (Interleaving the matrix
+    // instructions of neighbouring tiles with the vector work inside a wave, as the density sweep does, was built and
+    // measured: 25.1 us against 23.7 - the loop's vector pipe is already 83 % busy with three waves per SIMD covering
+    // each other's matrix phases, and the interleaved form needs more vector instructions.)
+    const int n = !tile_live ? 0 : (half ? max(nT - T0 - tA, 0) : tA);     // this wave's tiles (wave-uniform)
+    const int tbase = T0 + (half ? tA : 0);
+    constexpr int NA = 4 * NP;                 // matrix instructions of half a tile's P.V
+
+    f32x16_t sacc;                             // scores of the tile whose weights are formed next
+    uint32_t pkh[8], pkl[8];                   // weights, bf16 hi and lo
+    uint32_t vt[2][2 * NP][4];                 // V^T operands: [landmark half][32 head dimensions][8 landmarks of this lane's dimension]
+
+    // (-1, 0) and (0, -1) as bf16 pairs, kept in (scalar) registers: written as an immediate operand the first one is
+    // encoded as the inline constant -1.0, which this instruction reads as the fp32 pattern, i.e. as (0, -1)
+    uint32_t c10 = 0x0000BF80u, c01 = 0xBF800000u;
+    asm volatile("" : "+s"(c10), "+s"(c01));
+    const bf16x2_t kMinusOneZero = __builtin_bit_cast(bf16x2_t, c10);
+    const bf16x2_t kZeroMinusOne = __builtin_bit_cast(bf16x2_t, c01);
+
+    // weights of landmark pair w (score registers 2w, 2w + 1) as bf16 hi + bf16 lo (16 significant bits): one bf16 alone
+    // would cost up to 2^-9 relative error per weight, which is the whole error budget of the output
+    auto weights = [&](int w) {
+        f32x2_t pv;
+        pv[0] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w], scale_log2, -mref));
+        pv[1] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w + 1], scale_log2, -mref));
+        lrun += pv[0] + pv[1];
+        const bf16x2_t hi2 = __builtin_convertvector(pv, bf16x2_t);
+        // what the bf16 pair leaves of each weight, straight from the packed pair: p - hi.x * 1 - hi.y * 0 in one
+        // dot-product instruction (exact: the difference has at most 16 significant bits)
+        f32x2_t rest;
+        rest[0] = __builtin_amdgcn_fdot2_f32_bf16(hi2, kMinusOneZero, pv[0], false);
+        rest[1] = __builtin_amdgcn_fdot2_f32_bf16(hi2, kZeroMinusOne, pv[1], false);
+        pkh[w] = __builtin_bit_cast(uint32_t, hi2);
+        pkl[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
+    };
+    // matrix instruction i of landmark half kk2 of a tile's P.V: hi parts of every output tile first, then lo parts
+    auto pv_mfma = [&](int i, int kk2) {
+        const int lo = i / (2 * NP), p = i % (2 * NP);
+        const uint32_t *pk = lo ? pkl : pkh;
+        const bf16x8_t pf = __builtin_bit_cast(
+            bf16x8_t, make_uint4(pk[4 * kk2], pk[4 * kk2 + 1], pk[4 * kk2 + 2], pk[4 * kk2 + 3]));
+        const uint32_t *v = vt[kk2][p];
+        const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(v[0], v[1], v[2], v[3]));
+        oacc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[p], 0, 0, 0);
+    };
+    // K operand kk of the tile in the K slot of buffer `bi`: row nq, piece (2 kk + hb) ^ (nq & 7).  The row starts at a
+    // multiple of 16 CH bytes, so the swizzle is an XOR of the byte address with 32 kk: one address register, not NK.
+    // (this half's K slot is part of the lane's address, so that the buffer is an immediate offset)
+    const unsigned kaddr = ((unsigned)(nq * CH * 16) | (unsigned)(((nq & 7) ^ hb) * 16)) + (unsigned)(half * 2 * TP * 16);
+    auto read_k = [&](int bi, int kk) {
+        const char *sK = reinterpret_cast<const char *>(smem + bi * STG);
+        return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(sK + (kaddr ^ (unsigned)(32 * kk))));
+    };
+    // V^T operands of landmark half kk2 of the stage in buffer `bi`.  Contraction slot (kk2, hb, e) stands for landmark
+    // mfma_row(8 kk2 + e, hb) = 16 kk2 + 8 (e / 4) + 4 hb + e % 4 of the tile (the weights' registers fix that), i.e. a
+    // lane's 8 slots are two runs of 4 consecutive landmarks, and it needs them for ONE head dimension (32 p + nq).
+    // The transpose read works on blocks of 16 lanes: lane j of a block fetches 8 bytes, and lane i receives element
+    // i % 4 of the pieces fetched by lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4.  So lanes 4 e .. 4 e + 3 of a block
+    // fetch 16 consecutive head dimensions of landmark e of the run, and lane i comes away with dimension i of all
+    // four.  Blocks 0, 1 serve dimensions 0-15, 16-31 at hb = 0, blocks 2, 3 at hb = 1.  Rows of a run lie 2 D bytes
+    // apart, which would put them on the same banks: pieces are stored XOR-swizzled by row (see the copy above).  The
+    // swizzle depends on the row modulo 8 only, i.e. on the lane and not on the run, but it moves whole 32-dimension
+    // spans: one base address per span, the run an immediate offset.
+    const int vrow = 4 * hb + (lane & 15) / 4;                               // row of the run's first tile row + this
+    const int vdim = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);               // first of the 4 dimensions this lane fetches
+    const unsigned vswz = D == 64 ? ((vrow >> 1) & 1) << 2 : (vrow & 3) << 2;
+    unsigned vaddr[2 * NP];
 #pragma unroll
-    for (int kk = 0; kk < NK; ++kk) kslot[kk] = nq * CH + ((2 * kk + hb) ^ (nq & 7));
+    for (int p = 0; p < 2 * NP; ++p)
+        vaddr[p] = (unsigned)((half * 2 + 1) * TP * 16 + vrow * (int)RB) +
+                   ((((unsigned)(32 * p + vdim) >> 3) ^ vswz) * 16 + (vdim & 4) * 2);
+    auto read_v = [&](int bi, int kk2) {
+        typedef __attribute__((address_space(3))) s16x4_t *lds_s16x4;
+        const char *sV = reinterpret_cast<const char *>(smem + bi * STG);
+#pragma unroll
+        for (int p = 0; p < 2 * NP; ++p)
+#pragma unroll
+            for (int eh = 0; eh < 2; ++eh) {
+                const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(sV + vaddr[p] + (16 * kk2 + 8 * eh) * RB));
+                vt[kk2][p][2 * eh] = (uint32_t)(uint16_t)v[0] | ((uint32_t)(uint16_t)v[1] << 16);
+                vt[kk2][p][2 * eh + 1] = (uint32_t)(uint16_t)v[2] | ((uint32_t)(uint16_t)v[3] << 16);
+            }
+    };
+    // maximum of score registers [r0, r1) of `sc`, folded into tm
+    auto fold_max = [&](const f32x16_t &sc, float tm, int r0, int r1) {
+#pragma unroll
+        for (int r = r0; r < r1; ++r) tm = fmaxf(tm, sc[r]);
+        return tm;
+    };
+    // The scores in `sacc` are those of tile j (rows = landmarks, columns = queries), tm their maximum per lane: mask a
+    // ragged last tile, then move the reference maximum if some query of this wave exceeds it by more than 2^8.
+    auto settle = [&](int j, float tm) {
+        const int t0 = (tbase + j) * 32;
+        if (t0 + 32 > k) {       // ragged last tile: landmarks past k get zero weight
+            const int hbm = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) >> 5;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (t0 + mfma_row(r, hbm) >= k) sacc[r] = -__builtin_inff();
+            tm = fold_max(sacc, -__builtin_inff(), 0, 16);
+        }
+        float tmax = tm * scale_log2;
+        if (__any(tmax > mref + 8.0f)) {
+            // take the exact maximum over both half-columns (lane ^ 32 holds the other 16 landmarks) and rescale
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+            const float mnew = fmaxf(mref, fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])));
+            const float corr = __builtin_amdgcn_exp2f(mref - mnew);     // 0 on the first tile
+            mref = mnew;
+            lrun *= corr;
+#pragma unroll
+            for (int i = 0; i < 2 * NP; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+        }
+    };
+    auto scores_of = [&](int bi) {             // the tile in the K slot of buffer `bi` -> sacc, plain order
+        bf16x8_t kf[NK];
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) kf[kk] = read_k(bi, kk);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc, 0, 0, 0);
+    };
 
     // One stage: `bi` is its buffer (a constant at every call, so LDS offsets are immediates)
     auto stage = [&](int sidx, int bi) {
@@ -267,107 +385,17 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
             if constexpr (IDX) wait_vmcnt<NC + NI>();
             issue((bi + PF) % NBUF);
         }
-        const int t = T0 + (half ? tA + sidx : sidx);
-        if (!tile_live || t >= nT) return;             // wave-uniform
-        const int t0 = t * 32;
-        const uint4 *sK = smem + bi * STG + (half * 2 + 0) * TP;
-        const uint32_t *sV = reinterpret_cast<const uint32_t *>(smem + bi * STG + (half * 2 + 1) * TP);
-
-        bf16x8_t kf[NK];
+        if (sidx < n) {
+            read_v(bi, 0);
+            read_v(bi, 1);
+            scores_of(bi);
+            settle(sidx, fold_max(sacc, -__builtin_inff(), 0, 16));
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) kf[kk] = __builtin_bit_cast(bf16x8_t, sK[kslot[kk]]);
-        // V: the 32-bit word holding head dimensions (2 nq, 2 nq + 1) of 16 landmark rows; contraction slot
-        // (kk2, hb, e) <-> landmark t0 + mfma_row(8*kk2+e, hb) = t0 + 16 kk2 + 8 (e/4) + 4 hb + e%4.
-        uint32_t vd[2][NP][8];
+            for (int w = 0; w < 8; ++w) weights(w);
 #pragma unroll
-        for (int kk2 = 0; kk2 < 2; ++kk2)
+            for (int i = 0; i < NA; ++i) pv_mfma(i, 0);
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-#pragma unroll
-                for (int p = 0; p < NP; ++p)
-                    vd[kk2][p][e] = sV[(16 * kk2 + 8 * (e >> 2) + 4 * hb + (e & 3)) * (D / 2) + 32 * p + nq];
-
-        // ---- S^T tile: rows = landmarks t0..t0+31, columns = queries
-        f32x16_t sacc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sacc, 0, 0, 0);
-        if (t0 + 32 > k) {       // ragged last tile: landmarks past k get zero weight
-            asm volatile("" ::: "memory");              // (keeps this a branch: as selects it would run on every tile)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (t0 + mfma_row(r, hb) >= k) sacc[r] = -__builtin_inff();
-        }
-
-        // ---- online softmax, one query per lane (its other 16 landmarks sit in lane^32)
-        float tmax = sacc[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[r]);
-        tmax *= scale_log2;
-        if (__any(tmax > mref + 8.0f)) {
-            // some query of this wave moved: take the exact maximum over both half-columns and rescale
-            const float tm = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float mnew = fmaxf(mref, tm);
-            const float corr = __builtin_amdgcn_exp2f(mref - mnew);     // 0 on the first tile
-            mref = mnew;
-            lrun *= corr;
-#pragma unroll
-            for (int i = 0; i < 2 * NP; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
-        }
-        // probabilities as bf16 hi + bf16 lo (16 significant bits): one bf16 alone would cost up to
-        // 2^-9 relative error per weight, which is the whole error budget of the output
-        uint32_t pkh[8], pkl[8];
-        // (-1, 0) and (0, -1) as bf16 pairs, kept in registers: written as an immediate operand the first one is
-        // encoded as the inline constant -1.0, which this instruction reads as the fp32 pattern, i.e. as (0, -1)
-        uint32_t c10 = 0x0000BF80u, c01 = 0xBF800000u;
-        asm volatile("" : "+v"(c10), "+v"(c01));
-        const bf16x2_t kMinusOneZero = __builtin_bit_cast(bf16x2_t, c10);
-        const bf16x2_t kZeroMinusOne = __builtin_bit_cast(bf16x2_t, c01);
-        float psum = 0.0f;
-        const float nmref = -mref;
-#pragma unroll
-        for (int w = 0; w < 8; ++w) {
-            f32x2_t pv;
-            pv[0] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w], scale_log2, nmref));
-            pv[1] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * w + 1], scale_log2, nmref));
-            psum += pv[0] + pv[1];
-            const bf16x2_t hi2 = __builtin_convertvector(pv, bf16x2_t);
-            // what the bf16 pair leaves of each weight, straight from the packed pair: p - hi.x * 1 - hi.y * 0 in one
-            // dot-product instruction (exact: the difference has at most 16 significant bits)
-            f32x2_t rest;
-            rest[0] = __builtin_amdgcn_fdot2_f32_bf16(hi2, kMinusOneZero, pv[0], false);
-            rest[1] = __builtin_amdgcn_fdot2_f32_bf16(hi2, kZeroMinusOne, pv[1], false);
-            pkh[w] = __builtin_bit_cast(uint32_t, hi2);
-            pkl[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
-        }
-        lrun += psum;
-
-        // ---- O^T += Vs^T . P^T
-#pragma unroll
-        for (int kk2 = 0; kk2 < 2; ++kk2) {
-            const bf16x8_t pfh = __builtin_bit_cast(
-                bf16x8_t, make_uint4(pkh[4 * kk2], pkh[4 * kk2 + 1], pkh[4 * kk2 + 2], pkh[4 * kk2 + 3]));
-            const bf16x8_t pfl = __builtin_bit_cast(
-                bf16x8_t, make_uint4(pkl[4 * kk2], pkl[4 * kk2 + 1], pkl[4 * kk2 + 2], pkl[4 * kk2 + 3]));
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                uint32_t ev[4], od[4];
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    // low halves (even head dimension) and high halves (odd) of two landmark rows
-                    ev[w] = __builtin_amdgcn_perm(vd[kk2][p][2 * w + 1], vd[kk2][p][2 * w], 0x05040100u);
-                    od[w] = __builtin_amdgcn_perm(vd[kk2][p][2 * w + 1], vd[kk2][p][2 * w], 0x07060302u);
-                }
-                const bf16x8_t ve = __builtin_bit_cast(bf16x8_t, make_uint4(ev[0], ev[1], ev[2], ev[3]));
-                const bf16x8_t vo = __builtin_bit_cast(bf16x8_t, make_uint4(od[0], od[1], od[2], od[3]));
-                oacc[2 * p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ve, pfh, oacc[2 * p], 0, 0, 0);
-                oacc[2 * p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ve, pfl, oacc[2 * p], 0, 0, 0);
-                oacc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vo, pfh, oacc[2 * p + 1], 0, 0, 0);
-                oacc[2 * p + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vo, pfl, oacc[2 * p + 1], 0, 0, 0);
-            }
+            for (int i = 0; i < NA; ++i) pv_mfma(i, 1);
         }
     };
     for (int s0 = 0; s0 < tA; s0 += NBUF) {
@@ -377,20 +405,23 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     }
 
     // ---- merge the two halves of the landmark range: half 1 hands its state to half 0 through LDS
-    // (the merge area lies over the stage buffers: every wave is through with them first)
+    // (the merge area lies over the stage buffers: every wave is through with them first).  The lane's coordinates
+    // are derived afresh here, so that none of them holds a register across the loop above.
     __syncthreads();
+    const int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int hbe = ln >> 5;
     float(*xch)[NO + 2][64] = reinterpret_cast<float(*)[NO + 2][64]>(smem);
     if (half == 1) {
-        xch[wt][NO][lane] = mref;
-        xch[wt][NO + 1][lane] = lrun;
+        xch[wt][NO][ln] = mref;
+        xch[wt][NO + 1][ln] = lrun;
 #pragma unroll
         for (int i = 0; i < 2 * NP; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) xch[wt][i * 16 + r][lane] = oacc[i][r];
+            for (int r = 0; r < 16; ++r) xch[wt][i * 16 + r][ln] = oacc[i][r];
     }
     __syncthreads();
     if (half == 0 && tile_live) {
-        const float m1 = xch[wt][NO][lane], l1 = xch[wt][NO + 1][lane];
+        const float m1 = xch[wt][NO][ln], l1 = xch[wt][NO + 1][ln];
         const float mm = fmaxf(mref, m1);                 // finite: half 0 always holds landmark 0
         const float f0 = __builtin_amdgcn_exp2f(mref - mm), f1 = __builtin_amdgcn_exp2f(m1 - mm);
         float l = lrun * f0 + l1 * f1;
@@ -400,23 +431,21 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 #pragma unroll
         for (int i = 0; i < 2 * NP; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] = oacc[i][r] * g0 + xch[wt][i * 16 + r][lane] * g1;
-        if (valid) {
+            for (int r = 0; r < 16; ++r) oacc[i][r] = oacc[i][r] * g0 + xch[wt][i * 16 + r][ln] * g1;
+        const int me = tile * 32 + (ln & 31);             // this lane's query row of the head
+        if (me < M) {
             // one workgroup per landmark range: the result; several: a partial row [D values, maximum, denominator, pad]
-            const size_t rowid = (size_t)agent * Hq + qh;
+            int ge = g;                                   // (a fresh division: the first one's reciprocal is not kept)
+            asm volatile("" : "+s"(ge));
+            const size_t rowid = (size_t)(me / ge) * Hq + (h * ge + me % ge);
             float *orow = splits == 1 ? O + rowid * D : partial + ((size_t)sp * N * Hq + rowid) * (D + 4);
 #pragma unroll
-            for (int p = 0; p < NP; ++p)
+            for (int p = 0; p < 2 * NP; ++p)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    // registers 4b..4b+3 of the even and odd tile interleave into 8 consecutive dims
-                    float *dst = orow + 64 * p + 16 * b + 8 * hb;
-                    *reinterpret_cast<float4 *>(dst) = make_float4(oacc[2 * p][4 * b], oacc[2 * p + 1][4 * b],
-                                                                   oacc[2 * p][4 * b + 1], oacc[2 * p + 1][4 * b + 1]);
-                    *reinterpret_cast<float4 *>(dst + 4) = make_float4(oacc[2 * p][4 * b + 2], oacc[2 * p + 1][4 * b + 2],
-                                                                       oacc[2 * p][4 * b + 3], oacc[2 * p + 1][4 * b + 3]);
-                }
-            if (splits > 1 && hb == 0) *reinterpret_cast<float2 *>(orow + D) = make_float2(mm, l);
+                for (int b = 0; b < 4; ++b)      // registers 4b .. 4b+3 of tile p: dimensions 32 p + 8 b + 4 hb + 0 .. 3
+                    *reinterpret_cast<float4 *>(orow + 32 * p + 8 * b + 4 * hbe) =
+                        make_float4(oacc[p][4 * b], oacc[p][4 * b + 1], oacc[p][4 * b + 2], oacc[p][4 * b + 3]);
+            if (splits > 1 && hbe == 0) *reinterpret_cast<float2 *>(orow + D) = make_float2(mm, l);
         }
     }
 }

@@ -42,6 +42,8 @@ def test_headline_full_size(oracle):
     idx, score = ws.ws_synapse_select(K, rho, w.k, w.alpha, want_score=True)
     Ks, Vs = ws.ws_synapse_gather(K, V, idx)
     O = ws.ws_synapse_attend(Q, Ks, Vs)
+    # the one-pass form reads the same rows from the cache and must give the same bits
+    assert torch.equal(ws.ws_synapse_attend_indexed(Q, K, V, idx).view(torch.int32), O.view(torch.int32))
     torch.cuda.synchronize()
     print("GPU path done", flush=True)
 

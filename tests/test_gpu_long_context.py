@@ -47,6 +47,8 @@ def test_long_context_gqa_full_size(oracle):
     idx_stream = ws.ws_synapse_select(K, rho, w.k, w.alpha, kernel="stream")       # the other kernel, same inputs
     Ks, Vs = ws.ws_synapse_gather(K, V, idx)
     O = ws.ws_synapse_attend(Q, Ks, Vs)
+    # the one-pass form reads the same rows from the cache and must give the same bits
+    assert torch.equal(ws.ws_synapse_attend_indexed(Q, K, V, idx).view(torch.int32), O.view(torch.int32))
     torch.cuda.synchronize()
     print(f"GPU path done (selection: {'resident' if plan.resident else 'streaming'}, {plan.heads_in_flight} heads x "
           f"{plan.workgroups_per_head} workgroups)", flush=True)
