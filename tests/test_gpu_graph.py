@@ -25,6 +25,7 @@ def test_hot_path_under_graph_capture():
     Ks = torch.empty((w.H, w.k, w.d), dtype=torch.bfloat16, device=dev)
     Vs = torch.empty_like(Ks)
     O = torch.empty((w.N, w.Hq, w.d), dtype=torch.float32, device=dev)
+    O1 = torch.empty_like(O)              # the one-pass form (rows read from the cache by index)
     wd = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_DENSITY, dt, w.H, w.L, w.d), dtype=torch.uint8, device=dev)
     wsel = torch.empty(ws.ws_synapse_workspace_bytes(ws.WS_OP_SELECT, dt, w.H, w.L, w.d, w.k), dtype=torch.uint8, device=dev)
     sigma = [3.0] * w.H          # host values are baked into the captured launches: the same for every data set
@@ -34,6 +35,7 @@ def test_hot_path_under_graph_capture():
         ws.ws_synapse_select(K, rho, w.k, w.alpha, idx=idx, workspace=wsel, check=False)
         ws.ws_synapse_gather(K, V, idx, Ks=Ks, Vs=Vs)
         ws.ws_synapse_attend(Q, Ks, Vs, O=O)
+        ws.ws_synapse_attend_indexed(Q, K, V, idx, O=O1)
 
     def load(seed):
         Kh = np.stack([syn.cloud(w, h, syn.TENSOR_K, seed) for h in range(w.H)])
@@ -51,12 +53,13 @@ def test_hot_path_under_graph_capture():
         load(seed)
         run()                               # eager reference on the same buffers
         torch.cuda.synchronize()
-        ref = (rho.clone(), idx.clone(), Ks.clone(), Vs.clone(), O.clone())
-        for t in (rho, idx, Ks, Vs, O):
+        ref = (rho.clone(), idx.clone(), Ks.clone(), Vs.clone(), O.clone(), O1.clone())
+        assert torch.equal(O, O1)
+        for t in (rho, idx, Ks, Vs, O, O1):
             t.zero_()                       # eager work between replays; wipes the outputs
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         assert int(idx.min()) >= 0 and not ws.ws_synapse_select_failed(wsel)
-        for name, a, b in zip(("rho", "idx", "Ks", "Vs", "O"), (rho, idx, Ks, Vs, O), ref):
+        for name, a, b in zip(("rho", "idx", "Ks", "Vs", "O", "O (one pass)"), (rho, idx, Ks, Vs, O, O1), ref):
             assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager run"
