@@ -88,14 +88,15 @@ def density_with_report(ws, Kd, sigma):
     return rho, flagged, np.array(est)
 
 
+@pytest.mark.parametrize("cfg", [2, 4])               # head dimension 64 and 128
 @pytest.mark.parametrize("L", [2048, 600])            # the symmetric sweep and the full sweep
 @pytest.mark.parametrize("offset", [20.0, 100.0, -1000.0])
-def test_density_of_a_translated_cloud(ws, oracle, L, offset):
+def test_density_of_a_translated_cloud(ws, oracle, cfg, L, offset):
     """The density does not depend on where the cloud sits (the oracle pins that), and real key caches sit at an
     offset.  A cloud drawn around the origin is moved by a common offset BEFORE it is rounded to bf16, so the keys
     handed to both sides are the rounded, translated ones.  The Gram form alone would lose |offset|^2 d / sigma^2
     in accuracy (x 1e4 at offset 100); the library translates the head back exactly first."""
-    w = variant(2, H=3, L=L)
+    w = variant(cfg, H=3, L=L)
     rng = np.random.default_rng(int(abs(offset)) + L)
     K = np.empty((w.H, L, w.d), dtype=np.float32)
     for h in range(w.H):
@@ -115,7 +116,7 @@ def test_density_of_a_translated_cloud(ws, oracle, L, offset):
         print(f"offset {offset} L={L} head {h}: max rel err {err:.2e}; estimate {est[h]:.1e} "
               f"(uncentred it would be {2.0 ** -23 * norm:.1e})")
         assert err <= RHO_TOL["bf16"]
-        assert est[h] <= 1e-5
+        assert est[h] <= 2e-5              # the flag's threshold (coordinates that cannot move exactly keep their share)
     assert not flagged
 
 

@@ -62,3 +62,20 @@ def test_select_static_matches_select_on_two_calls_in_a_row():
         ws.ws_synapse_select_static(big, torch.ones((1, 600_000), device="cuda"), 4, 0.5,
                                     torch.empty((1, 4), dtype=torch.int32, device="cuda"))
     assert e.value.status == ws.WS_ERR_TOO_LARGE
+
+
+def test_select_static_on_a_wide_instance():
+    """A head that needs 128 workgroups (whole dies per head, four slots polled per lane) through the fixed array:
+    the same picks as with a caller-owned workspace, then a narrow shape on the used array."""
+    import torch
+    from paper_2601_01298_amd import binding as ws
+    ws.lib()
+    torch.manual_seed(5)
+    H, L, d, k = 2, 131072, 128, 48
+    plan = ws.ws_synapse_select_plan("auto", ws.WS_BF16, H, L, d)
+    assert plan.resident and plan.workgroups_per_head == 128
+    K = torch.randn((H, L, d), device="cuda").to(torch.bfloat16)
+    rho = torch.rand((H, L), device="cuda") * 0.9 + 0.05
+    both_ways(ws, torch, K, rho, k, 0.5)
+    K2 = K[:1, :5000].contiguous()
+    both_ways(ws, torch, K2, rho[:1, :5000].contiguous(), 30, 0.25)
