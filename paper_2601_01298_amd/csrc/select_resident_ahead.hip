@@ -451,7 +451,6 @@ select_resident(ResArgs a)
                     // ---- distance of every resident key to landmark `prev`: fetch of its row, then the screen.
                     // Both sit in one piece of code that takes the landmark's index, so that it can also run ahead
                     // of time for a landmark that is only expected (see the exchange below).
-                    const int wvl = tid >> 6;
                     unsigned needmask = 0u;          // bit r: this lane's key of row slot r may move
                     unsigned rowmask = 0u;           // bit r: some key of row slot r may move (wave-uniform)
                     float ns = 0.0f;                 // squared norm of the landmark (set once its pair has arrived)

@@ -64,21 +64,25 @@ def test_headline_full_size(oracle):
     assert bool((ref_Vs == Vs.view(torch.int16)).all())
     assert bool(torch.isfinite(O).all())
 
-    # ---- oracle on sampled rows: density of 16 rows in each of 8 heads
+    # ---- oracle on sampled rows: density of 16 rows in each of 48 heads (two per layer)
     rng = np.random.default_rng(2026)
     worst = 0.0
-    for h in [0, 1, 95, 191, 192, 300, 382, 383]:
+    row_heads = sorted({0, 1, 95, 191, 192, 300, 382, 383} | {16 * l + (7 * l + 2) % 16 for l in range(24)}
+                       | {16 * l + (3 * l + 11) % 16 for l in range(24)})
+    for h in row_heads:
         Kh = K[h].float().cpu().numpy()
         assert np.array_equal(Kh, syn.cloud(w, h, syn.TENSOR_K))          # same bits as the generator's
         rows = np.concatenate([rng.integers(0, w.L, 15), idx[h, :1].cpu().numpy()]).astype(np.int32)
         ref = oracle.density_rows(Kh, float(sigma[h]), rows)
         worst = max(worst, float(np.abs(rho[h].cpu().numpy()[rows] / ref - 1).max()))
-    print(f"density, 8 heads x 16 rows: max rel err {worst:.2e}", flush=True)
+    print(f"density, {len(row_heads)} heads x 16 rows: max rel err {worst:.2e}", flush=True)
     assert worst <= 5e-5
 
-    # ---- oracle on sampled heads: full chain (first and last head, first and last head of a layer, others)
+    # ---- oracle on sampled heads: full chain (first and last head, first and last head of a layer, and one head of
+    # every one of the 24 layers)
     forks_total, ties_total = 0, 0
-    for h in [0, 383, 137, 15, 16, 200, 287, 368]:
+    chain_heads = sorted({0, 383, 137, 15, 16, 200, 287, 368} | {16 * l + (5 * l + 3) % 16 for l in range(24)})
+    for h in chain_heads:
         Kh = K[h].float().cpu().numpy()
         Vh = V[h].float().cpu().numpy()
         rho_ref = oracle.density(Kh, float(sigma[h]))
@@ -94,8 +98,8 @@ def test_headline_full_size(oracle):
         assert err <= 5e-5 and aerr <= 2e-3
         forks_total += forks
         ties_total += int((gap < TIE_TOL).sum())
-    print(f"headline, 8 heads through the whole chain: {ties_total} near-tie steps survived, {forks_total} near-tie forks",
-          flush=True)
+    print(f"headline, {len(chain_heads)} heads through the whole chain: {ties_total} near-tie steps survived, "
+          f"{forks_total} near-tie forks", flush=True)
 
     # ---- the steps next to the hot path at the same full size
     # attention mass: all 24 layers in one call; oracle on 3 whole layers, sum rule on all
