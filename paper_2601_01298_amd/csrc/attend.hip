@@ -112,7 +112,7 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
             float *__restrict__ partial, const int32_t *__restrict__ idx, int L)
 {
     constexpr int NK = D / 16;   // k-steps of the score product
-    constexpr int NP = D / 64;   // 64-wide spans of head dimensions, each an even and an odd tile
+    constexpr int NP = D / 64;   // 64-wide spans of head dimensions, each two output tiles of 32 dimensions
     constexpr int CH = D / 8;    // 16-byte pieces per landmark row
     constexpr int TP = 32 * CH;  // pieces per 32-row tile
     constexpr int NLD = TP / 256;              // copies per thread and tile
@@ -248,8 +248,8 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
 
     // ---- the tile loop: scores, softmax weights and P.V of a tile one after the other.  (Interleaving the matrix
     // instructions of neighbouring tiles with the vector work inside a wave, as the density sweep does, was built and
-    // measured: 25.1 us against 23.7 - the loop's vector pipe is already 83 % busy with three waves per SIMD covering
-    // each other's matrix phases, and the interleaved form needs more vector instructions.)
+    // measured: 25.1 us against 23.7 - three waves per SIMD already cover each other's matrix phases, and the
+    // interleaved form needs 15 to 37 more vector instructions per tile.)
     const int n = !tile_live ? 0 : (half ? max(nT - T0 - tA, 0) : tA);     // this wave's tiles (wave-uniform)
     const int tbase = T0 + (half ? tA : 0);
     constexpr int NA = 4 * NP;                 // matrix instructions of half a tile's P.V
@@ -309,7 +309,7 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     // apart, which would put them on the same banks: pieces are stored XOR-swizzled by row (see the copy above).  The
     // swizzle depends on the row modulo 8 only, i.e. on the lane and not on the run, but it moves whole 32-dimension
     // spans: one base address per span, the run an immediate offset.
-    const int vrow = 4 * hb + (lane & 15) / 4;                               // row of the run's first tile row + this
+    const int vrow = 4 * hb + (lane & 15) / 4;                               // the row this lane fetches, counted from the run's base 16 kk2 + 8 eh
     const int vdim = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);               // first of the 4 dimensions this lane fetches
     const unsigned vswz = D == 64 ? ((vrow >> 1) & 1) << 2 : (vrow & 3) << 2;
     unsigned vaddr[2 * NP];
