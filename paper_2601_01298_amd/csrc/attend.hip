@@ -103,8 +103,8 @@ __device__ __forceinline__ void wait_vmcnt()
 // IDX: Ks / Vs are the whole cache [Hkv, L, D] and landmark t of head h is row idx[h, t] (clamped into [0, L)).
 // A thread then needs the index of each row it copies one step before the copy is issued: the indices of a stage
 // are asked for one stage earlier than its copies (into a ring of register sets, one per stage buffer), so the copy
-// never waits for the youngest load in flight.  Order of a thread's memory operations, PF = 2:
-//     idx(0) idx(1) Q | copies(0) idx(2) copies(1) | idx(3) copies(2) | idx(4) copies(3) | ...
+// never waits for the youngest load in flight.  Order of a thread's memory operations (one stage ahead):
+//     idx(0) idx(1) Q | copies(0) | idx(2) copies(1) | idx(3) copies(2) | ...
 template <int D, bool IDX>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2)))
 attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, const uint16_t *__restrict__ Vs,
@@ -116,7 +116,8 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     constexpr int CH = D / 8;    // 16-byte pieces per landmark row
     constexpr int TP = 32 * CH;  // pieces per 32-row tile
     constexpr int NLD = TP / 256;              // copies per thread and tile
-    constexpr int NBUF = D == 64 ? 3 : 2;      // stage buffers (a stage: K and V tile of both halves)
+    constexpr int NBUF = 2;                    // stage buffers (a stage: K and V tile of both halves); a third one, i.e. two
+                                               // stages in flight, is no faster at either head dimension (the loop does not wait for memory)
     constexpr int PF = NBUF - 1;               // stages in flight ahead of the one being read
     constexpr int NC = 4 * NLD;                // copies per thread and stage
     constexpr int NI = IDX ? 2 * NLD : 0;      // index loads per thread and stage
@@ -144,7 +145,10 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     const int lane = tid & 63, nq = lane & 31, hb = lane >> 5;
     const uint16_t *Kh = Ks + (size_t)h * (IDX ? L : k) * D;
     const uint16_t *Vh = Vs + (size_t)h * (IDX ? L : k) * D;
-    const int wt = wave & 1, half = wave >> 1;
+    // Which wave pair takes which half alternates from one group of 256 workgroups to the next (a compute unit's three
+    // workgroups come from three such groups): an odd tile count gives half 0 one tile more, and that tile should not
+    // land on the same two SIMDs three times.
+    const int wt = wave & 1, half = (wave >> 1) ^ (((blockIdx.x / splits) >> 8) & 1);
     const int tile = part * 2 + wt;
     const bool tile_live = tile * 32 < M;    // wave-uniform
     const int m = tile * 32 + nq;
