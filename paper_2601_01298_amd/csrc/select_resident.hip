@@ -87,11 +87,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
             // whole step loop they would be spilled and reloaded on this, the latency-critical path.
             int ln = lane;
             asm volatile("" : "+v"(ln));
-            if (ln < 2) {
-                const unsigned long long word =
-                    ln == 0 ? (((unsigned long long)md << 32) | tag) : (((unsigned long long)mh << 32) | ml | tag);
-                __hip_atomic_store(slot + ln * MS + member, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            post_words(slot, MS, member, ln, md, mh, ml, tag);
             unsigned touched = 0u;
             if (prefetch && ln < D / 8) {
                 // candidate index travels in bits 8..31 of lo, complemented
@@ -101,20 +97,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
             const int who = ln & 31, kind = ln >> 5;
             unsigned long long g = 0ull;
             if (!WIDE) {
-                bool ok = who >= nwg;
-                unsigned spins = 0;
-                while (true) {
-                    if (!ok) {
-                        g = __hip_atomic_load(slot + kind * MS + who, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ok = (unsigned)(g & 0xFFull) == tag;
-                    }
-                    if (__all(ok)) break;
-                    if (++spins > kSpinLimit) {
-                        good = false;
-                        break;
-                    }
-                    if (spins > 16) __builtin_amdgcn_s_sleep(1);
-                }
+                good = poll_members(slot, MS, nwg, ln, tag, g);
             } else {
                 // up to 128 members: a lane polls members who, who + 32, who + 64, who + 96 and keeps the largest word
                 // (tag bits cleared; for the D maxima the low half is empty, so one 64-bit comparison serves both kinds)
@@ -146,21 +129,7 @@ __device__ __forceinline__ bool head_max(unsigned dm, unsigned hi, unsigned lo, 
             }
             if (who >= nwg || !good) g = 0ull;
             const unsigned gh = (unsigned)(g >> 32), gl = (unsigned)g & 0xFFFFFF00u;
-            // lanes 0..31 hold the D maxima, lanes 32..63 the candidates: one row-wise pass serves both
-            {
-                unsigned v = gh;
-                v = dpp_umax<0xB1>(v);
-                v = dpp_umax<0x4E>(v);
-                v = dpp_umax<0x141>(v);
-                v = dpp_umax<0x140>(v);
-                const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
-                const unsigned r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
-                const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
-                const unsigned r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
-                md = r0 > r1 ? r0 : r1;
-                mh = r2 > r3 ? r2 : r3;
-            }
-            ml = wave_pick_lo(kind == 1 && gh == mh, gl);
+            fold_polled(gh, gl, ln, md, mh, ml);
             if (touched == 0xFFFFFFFFu && seq == 0u) good = false;   // never true: keeps the touch alive
         }
         if (lane == 0) {
@@ -498,48 +467,10 @@ select_resident(ResArgs a)
                             Dv[r] = fminf(Dv[r], __fsqrt_rn(acc));    // chosen keys stay at -1
                         }
                     }
-                    // ---- the staged keys of this wave, KPP per pass: LPK lanes share a key, each takes two
-                    // packed words of it and of the landmark row (both from LDS), direct differences in fp32,
-                    // then the partial sums of a key meet by DPP inside their lane group.  No barrier and no
-                    // atomic: since key blocks are dealt round-robin the waves of a head stage about the same
-                    // number of keys.
+                    // ---- the staged keys of this wave: exact distances, several keys per pass (evaluate_staged)
                     const int total = base;
                     if (total > 0) {
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        // lane-derived addresses are rebuilt here every step: hoisted out of the step loop they would
-                        // occupy registers that the resident keys need
-                        int ln = lane;
-                        asm volatile("" : "+v"(ln));
-                        // a lane takes packed words `part` and `part + LPK` of its key; of the landmark row it holds
-                        // one of the two already (lmw), the lane LPK further on holds the other
-                        const int sub = ln / LPK, part = ln % LPK;
-                        const uint32_t other = lmo;
-                        const bool odd = (sub & 1) != 0;
-                        const uint32_t wa = odd ? other : lmw, wb = odd ? lmw : other;
-                        const float l0 = __uint_as_float(wa << 16), l1 = __uint_as_float(wa & 0xFFFF0000u);
-                        const float l2 = __uint_as_float(wb << 16), l3 = __uint_as_float(wb & 0xFFFF0000u);
-                        for (int q0 = 0; q0 < total; q0 += KPP) {        // slots past `total` hold stale rows: computed, never used
-                            const uint32_t ka = stage[(q0 + sub) * DW + part], kb = stage[(q0 + sub) * DW + part + LPK];
-                            const float d0 = __uint_as_float(ka << 16) - l0, d1 = __uint_as_float(ka & 0xFFFF0000u) - l1;
-                            const float d2 = __uint_as_float(kb << 16) - l2, d3 = __uint_as_float(kb & 0xFFFF0000u) - l3;
-                            float pr = fmaf(d1, d1, d0 * d0) + fmaf(d3, d3, d2 * d2);
-                            pr = dpp_fadd<0xB1>(pr);
-                            pr = dpp_fadd<0x4E>(pr);
-                            pr = dpp_fadd<0x141>(pr);
-                            pr = dpp_fadd<0x140>(pr);          // every lane: the sum over its row of 16
-                            if (LPK == 16) {
-                                if (part == 0) sres[q0 + sub] = __fsqrt_rn(pr);
-                            } else {
-                                const float s0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 0));
-                                const float s1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 16));
-                                const float s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 32));
-                                const float s3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 48));
-                                if (ln < 2) sres[q0 + ln] = __fsqrt_rn(ln == 0 ? s0 + s1 : s2 + s3);
-                            }
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
+                        evaluate_staged<DW>(stage, sres, total, lane, lmw, lmo);
 #pragma unroll
                         for (int r = 0; r < R; ++r) {
                             if (stmask & (1u << r)) {

@@ -1,8 +1,10 @@
 // Pieces shared by the two register-resident selection kernels (select_resident.hip and
-// select_resident_ahead.hip): the launch arguments, the limits of the exchange protocol, and the
-// wave-level reductions both step loops are built from.  The step loops themselves stay in their
-// own files: the eight-rows-per-lane instance sits exactly at its register budget and is laid out
-// by hand.
+// select_resident_ahead.hip): the launch arguments, the exchange protocol between the workgroups
+// of a head (its limits, the post, the poll of up to 32 members, the fold of what was polled), the
+// pass over a wave's staged keys, and the wave-level reductions both step loops are built from.
+// The step loops themselves, and what each kernel does between post and poll, stay in their own
+// files: the eight-rows-per-lane instance sits exactly at its register budget and is laid out by
+// hand.
 #pragma once
 #include "ws_internal.h"
 
@@ -76,6 +78,109 @@ __device__ __forceinline__ unsigned wave_pick_lo(bool match, unsigned lo)
     const unsigned long long m = __ballot(match);
     if (__popcll(m) == 1) return (unsigned)__builtin_amdgcn_readlane((int)lo, (int)__builtin_ctzll(m));
     return wave_umax(match ? lo : 0u);
+}
+
+// ---- the exchange between the workgroups of a head ---------------------------------------------------------
+// Every workgroup owns two tagged 64-bit slots per phase, [kind][member]: kind 0 carries its D maximum
+// (value << 32 | tag), kind 1 its candidate (score bits << 32 | complemented index << 8 | tag).  One wave per
+// workgroup posts and polls; `ln` is that wave's lane id (rebuilt by the caller behind an empty statement, so the
+// addresses derived from it do not stay in registers across the step loop).
+
+// lanes 0 and 1 of the posting wave write the workgroup's two words
+__device__ __forceinline__ void post_words(unsigned long long *slot, int slots_per_kind, int member, int ln, unsigned md,
+                                           unsigned mh, unsigned ml, unsigned tag)
+{
+    if (ln < 2) {
+        const unsigned long long word =
+            ln == 0 ? (((unsigned long long)md << 32) | tag) : (((unsigned long long)mh << 32) | ml | tag);
+        __hip_atomic_store(slot + ln * slots_per_kind + member, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Up to 32 members: lane j polls the D maximum of member j, lane 32 + j its candidate, until every word carries
+// this exchange's tag or the bounded wait expires (returns false).  g: the word this lane polled.
+__device__ __forceinline__ bool poll_members(const unsigned long long *slot, int slots_per_kind, int nwg, int ln,
+                                             unsigned tag, unsigned long long &g)
+{
+    const int who = ln & 31, kind = ln >> 5;
+    bool ok = who >= nwg;
+    unsigned spins = 0;
+    g = 0ull;
+    while (true) {
+        if (!ok) {
+            g = __hip_atomic_load(slot + kind * slots_per_kind + who, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = (unsigned)(g & 0xFFull) == tag;
+        }
+        if (__all(ok)) return true;
+        if (++spins > kSpinLimit) return false;
+        if (spins > 16) __builtin_amdgcn_s_sleep(1);
+    }
+}
+
+// Fold of the polled words (high halves gh, low halves gl with the tag cleared; 0 in lanes without a member): lanes
+// 0..31 hold D maxima, lanes 32..63 candidates, so one row-wise pass serves both; the candidate's low half comes from
+// the lane whose high half won.
+__device__ __forceinline__ void fold_polled(unsigned gh, unsigned gl, int ln, unsigned &md, unsigned &mh, unsigned &ml)
+{
+    unsigned v = gh;
+    v = dpp_umax<0xB1>(v);
+    v = dpp_umax<0x4E>(v);
+    v = dpp_umax<0x141>(v);
+    v = dpp_umax<0x140>(v);
+    const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
+    const unsigned r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
+    const unsigned r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    md = r0 > r1 ? r0 : r1;
+    mh = r2 > r3 ? r2 : r3;
+    ml = wave_pick_lo((ln >> 5) == 1 && gh == mh, gl);
+}
+
+// ---- the staged keys of a wave ---------------------------------------------------------------------------------
+// `total` packed key rows (DW words each) wait in the wave's strip `stage`; their exact distances to the landmark go to
+// `sres`.  KPP = 64 / LPK keys per pass: LPK = DW / 2 lanes share a key, each takes two packed words of it (from the
+// strip) and of the landmark row (lmw: the word this lane already holds, lmo: the one the lane LPK further on holds),
+// direct differences in fp32, then the partial sums of a key meet by DPP inside their lane group.  No barrier and no
+// atomic: key blocks are dealt round-robin, so the waves of a head stage about the same number of keys.  Slots past
+// `total` hold stale rows: computed, never used.
+template <int DW>
+__device__ __forceinline__ void evaluate_staged(const uint32_t *stage, float *sres, int total, int lane, uint32_t lmw,
+                                                uint32_t lmo)
+{
+    constexpr int LPK = DW / 2;
+    constexpr int KPP = 64 / LPK;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // lane-derived addresses are rebuilt here every step: hoisted out of the step loop they would occupy registers
+    // that the resident keys need
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int sub = ln / LPK, part = ln % LPK;
+    const bool odd = (sub & 1) != 0;
+    const uint32_t wa = odd ? lmo : lmw, wb = odd ? lmw : lmo;
+    const float l0 = __uint_as_float(wa << 16), l1 = __uint_as_float(wa & 0xFFFF0000u);
+    const float l2 = __uint_as_float(wb << 16), l3 = __uint_as_float(wb & 0xFFFF0000u);
+    for (int q0 = 0; q0 < total; q0 += KPP) {
+        const uint32_t ka = stage[(q0 + sub) * DW + part], kb = stage[(q0 + sub) * DW + part + LPK];
+        const float d0 = __uint_as_float(ka << 16) - l0, d1 = __uint_as_float(ka & 0xFFFF0000u) - l1;
+        const float d2 = __uint_as_float(kb << 16) - l2, d3 = __uint_as_float(kb & 0xFFFF0000u) - l3;
+        float pr = fmaf(d1, d1, d0 * d0) + fmaf(d3, d3, d2 * d2);
+        pr = dpp_fadd<0xB1>(pr);
+        pr = dpp_fadd<0x4E>(pr);
+        pr = dpp_fadd<0x141>(pr);
+        pr = dpp_fadd<0x140>(pr);          // every lane: the sum over its row of 16
+        if (LPK == 16) {
+            if (part == 0) sres[q0 + sub] = __fsqrt_rn(pr);
+        } else {
+            const float s0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 0));
+            const float s1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 16));
+            const float s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 32));
+            const float s3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr), 48));
+            if (ln < 2) sres[q0 + ln] = __fsqrt_rn(ln == 0 ? s0 + s1 : s2 + s3);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 }  // namespace resident

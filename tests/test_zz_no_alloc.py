@@ -18,10 +18,11 @@ def both_ways(ws, torch, K, rho, k, alpha):
     idx = torch.full((H, k), -7, dtype=torch.int32, device="cuda")
     score = torch.zeros((H, k), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    allocations = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]     # a count: frees do not move it
+    before = allocations()
     ws.ws_synapse_select_static(K, rho, k, alpha, idx, score_out=score)
     assert not ws.ws_synapse_select_failed(None)
-    assert torch.cuda.memory_allocated() == before            # nothing came from torch's allocator either
+    assert allocations() == before                             # nothing came from torch's allocator either
     assert int(idx.min()) >= 0
     assert torch.equal(idx, ref), "landmarks differ between the two entry points"
     assert torch.equal(score, ref_score)
