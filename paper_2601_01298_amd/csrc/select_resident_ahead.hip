@@ -442,97 +442,12 @@ select_resident(ResArgs a)
                         fetch_screen(prev, lws, lmw, lmo, needmask, rowmask, ns, std::false_type{});
                     }
                     spec_idx = -1;
-                    // row slots whose keys no longer fit the wave's staging strip (the first steps, when most keys
-                    // move) are evaluated whole instead
-                    int base = 0;
                     // the wave's strips are located afresh in every step: kept across the step loop their addresses
                     // end up in scratch
                     int wl = tid >> 6;
                     asm volatile("" : "+v"(wl));
-                    uint32_t *stage = stage_all[wl];
-                    float *sres = sres_all[wl];
-                    unsigned pm0 = 0u, pm1 = 0u;     // per row slot, 1 + the staging position of this lane's key
-                    float lmax;
-                    unsigned stmask = 0u;            // bit r: row slot r has keys in the staging area (wave-uniform)
-                    rowmask = __builtin_amdgcn_readfirstlane(rowmask);
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        if (!(rowmask & (1u << r))) continue;
-                        const bool need = (needmask >> r) & 1u;
-                        const unsigned long long bal = __ballot(need);
-                        const int cnt = __popcll(bal);
-                        if (cnt <= CAP - base) {
-                            stmask |= 1u << r;
-                            // (b) A few keys of the slot may move (the usual case: about 1 % of all keys per
-                            // step): their owners copy the packed rows to the wave's staging strip.
-                            const int pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32),
-                                                                                  __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
-                            base += cnt;
-                            if (need) {
-#pragma unroll
-                                for (int c = 0; c < NV; ++c) {
-                                    uint4 q;
-                                    if (r < RREG) {
-                                        q = make_uint4(kr[r < RREG ? r : 0][4 * c], kr[r < RREG ? r : 0][4 * c + 1],
-                                                       kr[r < RREG ? r : 0][4 * c + 2], kr[r < RREG ? r : 0][4 * c + 3]);
-                                    } else {
-                                        q = lrows[((r - RREG) * NV + c) * 256 + tid];
-                                    }
-                                    *reinterpret_cast<uint4 *>(&stage[pos * DW + 4 * c]) = q;
-                                    if (r >= RREG) __builtin_amdgcn_sched_barrier(0);
-                                }
-                                if (r < 4) pm0 |= (unsigned)(pos + 1) << (8 * (r & 3));
-                                else pm1 |= (unsigned)(pos + 1) << (8 * (r & 3));
-                            }
-                        } else {
-                            // (c) Many keys of the slot may move: the whole slot, each lane its own key,
-                            // direct coordinate differences in fp32.
-                            float acc = 0.0f;
-#pragma unroll
-                            for (int c = 0; c < NV; ++c) {
-                                uint32_t w4[4];
-                                if (r < RREG) {
-                                    w4[0] = kr[r < RREG ? r : 0][4 * c];
-                                    w4[1] = kr[r < RREG ? r : 0][4 * c + 1];
-                                    w4[2] = kr[r < RREG ? r : 0][4 * c + 2];
-                                    w4[3] = kr[r < RREG ? r : 0][4 * c + 3];
-                                } else {
-                                    const uint4 q = lrows[((r - RREG) * NV + c) * 256 + tid];
-                                    w4[0] = q.x;
-                                    w4[1] = q.y;
-                                    w4[2] = q.z;
-                                    w4[3] = q.w;
-                                }
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) {
-                                    const uint32_t wd = lws[4 * c + j];
-                                    const float d0 = __uint_as_float(w4[j] << sh16) - __uint_as_float(wd << 16);
-                                    acc = fmaf(d0, d0, acc);
-                                    const float d1 = __uint_as_float(w4[j] & mhi16) - __uint_as_float(wd & 0xFFFF0000u);
-                                    acc = fmaf(d1, d1, acc);
-                                }
-                                if (r >= RREG) __builtin_amdgcn_sched_barrier(0);
-                            }
-                            Dv[r] = fminf(Dv[r], __fsqrt_rn(acc));    // chosen keys stay at -1
-                        }
-                    }
-                    // ---- the staged keys of this wave: exact distances, several keys per pass (evaluate_staged)
-                    const int total = base;
-                    if (total > 0) {
-                        evaluate_staged<DW>(stage, sres, total, lane, lmw, lmo);
-#pragma unroll
-                        for (int r = 0; r < R; ++r) {
-                            if (stmask & (1u << r)) {
-                                const unsigned pb = ((r < 4 ? pm0 : pm1) >> (8 * (r & 3))) & 0xFFu;
-                                const float dn = sres[pb ? pb - 1 : 0];
-                                if (pb) Dv[r] = fminf(Dv[r], dn);    // chosen keys stay at -1
-                            }
-                        }
-                    }
-                    lmax = 0.0f;
-#pragma unroll
-                    for (int r = 0; r < R; ++r) lmax = fmaxf(lmax, Dv[r]);
-                    lbits = wave_umax(__float_as_uint(lmax));
+                    lbits = exact_update<D, RREG, RLDS, CAP>(kr, lrows, lws, Dv, needmask, rowmask, stage_all[wl], sres_all[wl], tid,
+                                                            lane, lmw, lmo, sh16, mhi16);
                 }
 
                 int s;
