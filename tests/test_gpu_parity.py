@@ -415,6 +415,10 @@ def test_gather_is_bit_exact(ws, oracle, dtype, d):
 @pytest.mark.parametrize("dtype,N,Hq,Hkv,k,d", [
     ("bf16", 100, 16, 16, 82, 64), ("bf16", 7, 8, 2, 33, 64), ("bf16", 33, 4, 4, 1, 64),
     ("bf16", 50, 8, 2, 164, 128), ("bf16", 256, 4, 1, 655, 64),
+    ("bf16", 1, 1, 1, 32, 64),                # one query, exactly one tile (half 1 has none)
+    ("bf16", 3, 48, 24, 64, 64),              # heads dealt to the dies, one tile per half
+    ("bf16", 65, 2, 2, 31, 128),              # a third query tile with one live row, a single ragged tile
+    ("bf16", 130, 8, 8, 97, 128),             # four tiles, the last ragged, five query tiles
     ("f32", 4, 1, 1, 10, 64), ("f32", 5, 6, 3, 130, 128),
 ])
 def test_attend_matches_oracle(ws, oracle, dtype, N, Hq, Hkv, k, d):
@@ -440,6 +444,8 @@ def test_attend_matches_oracle(ws, oracle, dtype, N, Hq, Hkv, k, d):
     ("bf16", 256, 4, 1, 20000, 655, 64),      # few heads, many landmarks: 21 stages
     ("bf16", 64, 8, 2, 9000, 2621, 128),      # landmark range split over workgroups, merged from the workspace
     ("bf16", 40, 4, 4, 64, 64, 64),           # k = L: every row, in pick order
+    ("bf16", 1, 8, 8, 77, 32, 64),            # one query; heads dealt to the dies
+    ("bf16", 65, 2, 2, 500, 31, 128),         # a single ragged tile at d = 128
     ("f32", 4, 1, 1, 100, 10, 64), ("f32", 5, 6, 3, 500, 130, 128),
 ])
 def test_attend_indexed_is_gather_then_attend(ws, oracle, dtype, N, Hq, Hkv, L, k, d):
