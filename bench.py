@@ -186,6 +186,16 @@ def main() -> int:
         "attend": {"bound": "hbm", "achieved": bytes_attend / (stage_ms["attend"] * 1e-3) / 1e9,
                    "peak": PEAK_HBM_GBS, "unit": "GB/s"},
     }
+    if bf16:
+        # The attention kernel is priced against HBM as the stage's table row asks, but at 100 query rows per head what
+        # bounds it is instruction issue: per 32 x 32 tile a SIMD spends about 444 cycles of vector work and 384 of
+        # matrix work (12 MFMAs of 32 cycles), nearly in series; 33 such tiles per SIMD at the headline.
+        tiles = ((w.N * (w.Hq // w.H) + 31) // 32) * ((w.k + 31) // 32) * w.H
+        per_stage["attend"]["alu"] = {"bound": "alu + mfma in series", "cycles_per_tile": 828 if w.d == 64 else None,
+                                      "tiles_per_simd": tiles / 1024.0,
+                                      "floor_ms": (tiles / 1024.0 * 828 / 2.4e9 * 1e3) if w.d == 64 else None}
+        if w.d == 64:
+            per_stage["attend"]["alu"]["frac_back_to_back"] = per_stage["attend"]["alu"]["floor_ms"] / b2b["attend"]
     sym = ws.ws_synapse_density_is_symmetric(dt, w.L, w.d)      # the library's own choice of sweep
     if sym:
         # What the sweep is bound by in practice is the vector pipe, not the matrix core: every unordered pair
