@@ -472,6 +472,29 @@ def test_attend_indexed_is_gather_then_attend(ws, oracle, dtype, N, Hq, Hkv, L, 
     assert torch.equal(O3.view(torch.int32), ws.ws_synapse_attend(Qd, Ks, Vs, scale=0.05).view(torch.int32))
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 128), ("f32", 64)])
+def test_indices_outside_the_cache_are_clamped(ws, dtype, d):
+    """The boundary promises that an index outside [0, L) is clamped into range rather than followed (a selection that
+    gave up leaves -1 behind): gather and the one-pass attention must give what they give for the clamped indices."""
+    import torch
+    rng = np.random.default_rng(29)
+    H, L, k, N = 3, 500, 70, 9
+    def draw(*shape):
+        x = rng.standard_normal(shape).astype(np.float32)
+        return syn.round_to_bf16(x) if dtype == "bf16" else x
+    K, V, Q = to_device(draw(H, L, d), dtype), to_device(draw(H, L, d), dtype), to_device(draw(N, H, d), dtype)
+    idx = np.stack([rng.permutation(L)[:k] for _ in range(H)]).astype(np.int32)
+    idx[0, 3], idx[0, 40], idx[1, 0], idx[1, 69], idx[2, 33], idx[2, 34] = -1, L, -2**31, 2**31 - 1, L + 7, -5
+    good = torch.from_numpy(np.clip(idx, 0, L - 1)).cuda()
+    bad = torch.from_numpy(idx).cuda()
+    Ks, Vs = ws.ws_synapse_gather(K, V, bad)
+    Ks_ref, Vs_ref = ws.ws_synapse_gather(K, V, good)
+    assert torch.equal(Ks.view(torch.uint8), Ks_ref.view(torch.uint8)) and torch.equal(Vs.view(torch.uint8), Vs_ref.view(torch.uint8))
+    O = ws.ws_synapse_attend_indexed(Q, K, V, bad)
+    assert torch.equal(O.view(torch.int32), ws.ws_synapse_attend_indexed(Q, K, V, good).view(torch.int32))
+    assert torch.equal(O.view(torch.int32), ws.ws_synapse_attend(Q, Ks_ref, Vs_ref).view(torch.int32))
+
+
 # ------------------------------------------------------------------------- whole chain
 @pytest.mark.parametrize("cfg", [1, 2])
 def test_chain_small_configs(ws, oracle, cfg):
