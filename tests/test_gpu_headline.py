@@ -63,6 +63,15 @@ def test_headline_full_size(oracle):
     ref_Vs = torch.gather(V.view(torch.int16), 1, idx.long()[:, :, None].expand(-1, -1, w.d))
     assert bool((ref_Vs == Vs.view(torch.int16)).all())
     assert bool(torch.isfinite(O).all())
+    # attention on ALL heads against the oracle, over the rows the library gathered (bit copies, just checked): the
+    # oracle's attention is cheap at k rows per head
+    Ks_h, Vs_h, O_h = Ks.float().cpu().numpy(), Vs.float().cpu().numpy(), O.cpu().numpy()
+    worst_att = 0.0
+    for h0 in range(0, w.H, 16):
+        O_ref = oracle.attend(Qh[:, h0:h0 + 16], Ks_h[h0:h0 + 16], Vs_h[h0:h0 + 16])
+        worst_att = max(worst_att, attn_rel_err(O_h[:, h0:h0 + 16], O_ref))
+    print(f"attention, all {w.H} heads: max rel err {worst_att:.2e}", flush=True)
+    assert worst_att <= 2e-3
 
     # ---- oracle on sampled rows: density of 16 rows in each of 48 heads (two per layer)
     rng = np.random.default_rng(2026)
