@@ -73,18 +73,22 @@ def test_headline_full_size(oracle):
     print(f"attention, all {w.H} heads: max rel err {worst_att:.2e}", flush=True)
     assert worst_att <= 2e-3
 
-    # ---- oracle on sampled rows: density of 16 rows in each of 48 heads (two per layer)
+    # ---- oracle on sampled rows: density of 8 rows in every head, 16 in 55 of them (two per layer and the corners)
     rng = np.random.default_rng(2026)
     worst = 0.0
     row_heads = sorted({0, 1, 95, 191, 192, 300, 382, 383} | {16 * l + (7 * l + 2) % 16 for l in range(24)}
                        | {16 * l + (3 * l + 11) % 16 for l in range(24)})
-    for h in row_heads:
+    rho_h = rho.cpu().numpy()
+    for h in range(w.H):
         Kh = K[h].float().cpu().numpy()
-        assert np.array_equal(Kh, syn.cloud(w, h, syn.TENSOR_K))          # same bits as the generator's
-        rows = np.concatenate([rng.integers(0, w.L, 15), idx[h, :1].cpu().numpy()]).astype(np.int32)
+        if h in row_heads:
+            assert np.array_equal(Kh, syn.cloud(w, h, syn.TENSOR_K))          # same bits as the generator's
+        nrows = 15 if h in row_heads else 7
+        rows = np.concatenate([rng.integers(0, w.L, nrows), idx[h, :1].cpu().numpy()]).astype(np.int32)
         ref = oracle.density_rows(Kh, float(sigma[h]), rows)
-        worst = max(worst, float(np.abs(rho[h].cpu().numpy()[rows] / ref - 1).max()))
-    print(f"density, {len(row_heads)} heads x 16 rows: max rel err {worst:.2e}", flush=True)
+        worst = max(worst, float(np.abs(rho_h[h][rows] / ref - 1).max()))
+    print(f"density, sampled rows of all {w.H} heads (16 in {len(row_heads)} of them, 8 in the others): max rel err {worst:.2e}",
+          flush=True)
     assert worst <= 5e-5
 
     # ---- oracle on sampled heads: full chain (first and last head, first and last head of a layer, and one head of
