@@ -63,8 +63,10 @@ def test_headline_full_size(oracle):
     ref_Vs = torch.gather(V.view(torch.int16), 1, idx.long()[:, :, None].expand(-1, -1, w.d))
     assert bool((ref_Vs == Vs.view(torch.int16)).all())
     assert bool(torch.isfinite(O).all())
-    # attention on ALL heads against the oracle, over the rows the library gathered (bit copies, just checked): the
-    # oracle's attention is cheap at k rows per head
+    # attention on ALL heads against the oracle, as a stage on identical inputs: the rows are the input keys' rows at the
+    # chosen positions (bit copies, just checked), the oracle's attention is cheap at k rows per head.  (Whether the
+    # positions are the right ones is the business of the full-chain comparison below, which feeds the oracle's own
+    # density and picks forward.)
     Ks_h, Vs_h, O_h = Ks.float().cpu().numpy(), Vs.float().cpu().numpy(), O.cpu().numpy()
     worst_att = 0.0
     for h0 in range(0, w.H, 16):
