@@ -1,5 +1,5 @@
 """Writes the oracle's full-size density of the long-context configuration (8 KV heads, d = 128,
-L = 131072, bf16 keys), heads 0, 3, 4 and 7, to tests/golden/long_context_density_h{0,3,4,7}.npz.
+L = 131072, bf16 keys), to tests/golden/long_context_density_h{0..7}.npz.
 
 The greedy chain of a head needs the density of all L keys, and the float64 oracle needs several
 minutes of CPU time per head for it at this size (L^2 d = 2.2e12 multiply-adds), too long to sit
@@ -32,7 +32,7 @@ def key_checksum(K: np.ndarray) -> int:
 
 
 def main():
-    heads = [int(a) for a in sys.argv[1:]] or [0, 3, 4, 7]
+    heads = [int(a) for a in sys.argv[1:]] or list(range(8))
     w = syn.WORKLOADS[5]
     oracle.build()
     for h in heads:
