@@ -407,6 +407,9 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
         for (int bi = 0; bi < NBUF; ++bi)
             if (s0 + bi < tA) stage(s0 + bi, bi);
     }
+    // The last stages have asked for indices that no copy will use.  Those loads are invisible to the compiler, which
+    // is free to give their destination registers to something else from here on: they must have landed first.
+    if constexpr (IDX) wait_vmcnt<0>();
 
     // ---- merge the two halves of the landmark range: half 1 hands its state to half 0 through LDS
     // (the merge area lies over the stage buffers: every wave is through with them first).  The lane's coordinates
