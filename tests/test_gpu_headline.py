@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.timeout(900)
-def test_headline_full_size(oracle):
+def test_headline_full_size(oracle, say):
     import torch
     from concurrent.futures import ThreadPoolExecutor
     from paper_2601_01298_amd import binding as ws
@@ -36,7 +36,7 @@ def test_headline_full_size(oracle):
     K, V = fill(syn.TENSOR_K), fill(syn.TENSOR_V)
     Qh = syn.queries(w)
     Q = torch.from_numpy(Qh).to(torch.bfloat16).cuda()
-    print(f"inputs resident: K,V {tuple(K.shape)} bf16, Q {tuple(Q.shape)}", flush=True)
+    say(f"inputs resident: K,V {tuple(K.shape)} bf16, Q {tuple(Q.shape)}")
 
     rho = ws.ws_synapse_density(K, [float(s) for s in sigma])
     idx, score = ws.ws_synapse_select(K, rho, w.k, w.alpha, want_score=True)
@@ -45,7 +45,7 @@ def test_headline_full_size(oracle):
     # the one-pass form reads the same rows from the cache and must give the same bits
     assert torch.equal(ws.ws_synapse_attend_indexed(Q, K, V, idx).view(torch.int32), O.view(torch.int32))
     torch.cuda.synchronize()
-    print("GPU path done", flush=True)
+    say("GPU path done")
 
     # ---- properties on ALL heads
     assert float(rho.min()) >= (1.0 / w.L) * (1 - 1e-5) and float(rho.max()) <= 1.0 + 1e-5
@@ -72,7 +72,7 @@ def test_headline_full_size(oracle):
     for h0 in range(0, w.H, 16):
         O_ref = oracle.attend(Qh[:, h0:h0 + 16], Ks_h[h0:h0 + 16], Vs_h[h0:h0 + 16])
         worst_att = max(worst_att, attn_rel_err(O_h[:, h0:h0 + 16], O_ref))
-    print(f"attention, all {w.H} heads: max rel err {worst_att:.2e}", flush=True)
+    say(f"attention, all {w.H} heads: max rel err {worst_att:.2e}")
     assert worst_att <= 2e-3
 
     # ---- oracle on sampled rows: density of 8 rows in every head, 16 in 55 of them (two per layer and the corners)
@@ -89,8 +89,7 @@ def test_headline_full_size(oracle):
         rows = np.concatenate([rng.integers(0, w.L, nrows), idx[h, :1].cpu().numpy()]).astype(np.int32)
         ref = oracle.density_rows(Kh, float(sigma[h]), rows)
         worst = max(worst, float(np.abs(rho_h[h][rows] / ref - 1).max()))
-    print(f"density, sampled rows of all {w.H} heads (16 in {len(row_heads)} of them, 8 in the others): max rel err {worst:.2e}",
-          flush=True)
+    say(f"density, sampled rows of all {w.H} heads (16 in {len(row_heads)} of them, 8 in the others): max rel err {worst:.2e}")
     assert worst <= 5e-5
 
     # ---- oracle on sampled heads: full chain (first and last head, first and last head of a layer, and four heads of
@@ -109,13 +108,13 @@ def test_headline_full_size(oracle):
         assert np.array_equal(Ks[h].float().cpu().numpy(), ks) and np.array_equal(Vs[h].float().cpu().numpy(), vs)
         O_ref = oracle.attend(Qh[:, h:h + 1], ks[None], vs[None])
         aerr = attn_rel_err(O[:, h:h + 1].cpu().numpy(), O_ref)
-        print(f"head {h}: density rel err {err:.2e}; oracle steps under tie tolerance {(gap < TIE_TOL).sum()}, "
-              f"forks {forks}; attention rel err {aerr:.2e}", flush=True)
+        say(f"head {h}: density rel err {err:.2e}; oracle steps under tie tolerance {(gap < TIE_TOL).sum()}, "
+              f"forks {forks}; attention rel err {aerr:.2e}")
         assert err <= 5e-5 and aerr <= 2e-3
         forks_total += forks
         ties_total += int((gap < TIE_TOL).sum())
-    print(f"headline, {len(chain_heads)} heads through the whole chain: {ties_total} near-tie steps survived, "
-          f"{forks_total} near-tie forks", flush=True)
+    say(f"headline, {len(chain_heads)} heads through the whole chain: {ties_total} near-tie steps survived, "
+          f"{forks_total} near-tie forks")
 
     # ---- the steps next to the hot path at the same full size
     # attention mass: all 24 layers in one call; oracle on 3 whole layers, sum rule on all
@@ -132,7 +131,7 @@ def test_headline_full_size(oracle):
         got = A[grp * Hl].double().cpu().numpy()
         big = ref > 1e-12 * ref.max()
         worst = max(worst, float(np.abs(got[big] / ref[big] - 1).max()))
-    print(f"attention mass, 3 of {G} layers: max rel err {worst:.2e}", flush=True)
+    say(f"attention mass, 3 of {G} layers: max rel err {worst:.2e}")
     assert worst <= 1e-4
 
     # density refresh: the last 3 rows of every head treated as just appended; oracle on sampled rows
@@ -141,7 +140,7 @@ def test_headline_full_size(oracle):
     rho_old = ws.ws_synapse_density(K[:, :w.L - m].contiguous(), sig)
     rho_new = ws.ws_synapse_density_append(K, m, sig, rho_old)
     diff = float((rho_new / rho - 1).abs().max())
-    print(f"density refresh (m={m}) vs full density on all {w.H} heads: max rel diff {diff:.2e}", flush=True)
+    say(f"density refresh (m={m}) vs full density on all {w.H} heads: max rel diff {diff:.2e}")
     assert diff <= 1e-4                                   # two GPU paths, each within 5e-5 of the oracle
     worst = 0.0
     for h in [0, 200, 383]:
@@ -149,5 +148,5 @@ def test_headline_full_size(oracle):
         rows = np.concatenate([rng.integers(0, w.L - m, 13), np.arange(w.L - m, w.L)]).astype(np.int32)
         ref = oracle.density_rows(Kh, sig[h], rows)
         worst = max(worst, float(np.abs(rho_new[h].cpu().numpy()[rows] / ref - 1).max()))
-    print(f"density refresh, 3 heads x 16 rows (new rows included): max rel err {worst:.2e}", flush=True)
+    say(f"density refresh, 3 heads x 16 rows (new rows included): max rel err {worst:.2e}")
     assert worst <= 5e-5

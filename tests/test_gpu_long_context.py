@@ -26,7 +26,7 @@ def key_checksum(K):
 
 
 @pytest.mark.timeout(900)
-def test_long_context_gqa_full_size(oracle):
+def test_long_context_gqa_full_size(oracle, say):
     import torch
     from paper_2601_01298_amd import binding as ws
     ws.lib()
@@ -39,7 +39,7 @@ def test_long_context_gqa_full_size(oracle):
     K = torch.from_numpy(Kh).to(torch.bfloat16).cuda()
     V = torch.from_numpy(Vh).to(torch.bfloat16).cuda()
     Q = torch.from_numpy(Qh).to(torch.bfloat16).cuda()
-    print(f"inputs resident: K,V {tuple(K.shape)} bf16, Q {tuple(Q.shape)}", flush=True)
+    say(f"inputs resident: K,V {tuple(K.shape)} bf16, Q {tuple(Q.shape)}")
 
     plan = ws.ws_synapse_select_plan("auto", ws.WS_BF16, w.H, w.L, w.d)
     rho = ws.ws_synapse_density(K, sigma)
@@ -50,8 +50,8 @@ def test_long_context_gqa_full_size(oracle):
     # the one-pass form reads the same rows from the cache and must give the same bits
     assert torch.equal(ws.ws_synapse_attend_indexed(Q, K, V, idx).view(torch.int32), O.view(torch.int32))
     torch.cuda.synchronize()
-    print(f"GPU path done (selection: {'resident' if plan.resident else 'streaming'}, {plan.heads_in_flight} heads x "
-          f"{plan.workgroups_per_head} workgroups)", flush=True)
+    say(f"GPU path done (selection: {'resident' if plan.resident else 'streaming'}, {plan.heads_in_flight} heads x "
+          f"{plan.workgroups_per_head} workgroups)")
 
     # ---- properties on all heads
     assert float(rho.min()) >= (1.0 / w.L) * (1 - 1e-5) and float(rho.max()) <= 1.0 + 1e-5
@@ -75,7 +75,7 @@ def test_long_context_gqa_full_size(oracle):
         rows = np.concatenate([rng.integers(0, w.L, 30), idx_h[h, :1], [int(rho_h[h].argmax())]]).astype(np.int32)
         ref = oracle.density_rows(Kh[h], sigma[h], rows)
         worst = max(worst, float(np.abs(rho_h[h][rows] / ref - 1).max()))
-    print(f"density, {w.H} heads x 32 rows: max rel err {worst:.2e}", flush=True)
+    say(f"density, {w.H} heads x 32 rows: max rel err {worst:.2e}")
     assert worst <= 5e-5
 
     # ---- every head: the stored oracle density, then the oracle's chain, gather and attention
@@ -96,7 +96,7 @@ def test_long_context_gqa_full_size(oracle):
         ties = int((gap < TIE_TOL).sum())
         forks_total += forks
         ties_total += ties
-        print(f"head {h}: density rel err over all {w.L} keys {err:.2e}; oracle steps under tie tolerance {ties}, "
-              f"forks {forks} (streaming kernel: {forks_s}); attention rel err (N={w.N}, {g} query heads) {aerr:.2e}", flush=True)
+        say(f"head {h}: density rel err over all {w.L} keys {err:.2e}; oracle steps under tie tolerance {ties}, "
+              f"forks {forks} (streaming kernel: {forks_s}); attention rel err (N={w.N}, {g} query heads) {aerr:.2e}")
         assert err <= 5e-5 and aerr <= 2e-3
-    print(f"long-context config: {ties_total} near-tie steps survived, {forks_total} near-tie forks on {w.H} heads", flush=True)
+    say(f"long-context config: {ties_total} near-tie steps survived, {forks_total} near-tie forks on {w.H} heads")
