@@ -23,6 +23,8 @@
 // Both paths also exist in an indexed form that reads the chosen rows K[h, idx[h,t], :] straight from the
 // cache (Sec. 3.3: the synapse holds the landmark rows only), so a caller that does not need the synapse as a
 // buffer of its own skips the gather pass: same arithmetic in the same order, bit-identical output.
+#include <type_traits>
+
 #include "ws_internal.h"
 
 namespace ws {
@@ -235,13 +237,15 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     for (int kk = 0; kk < NK; ++kk)
         asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(qw[kk]) : "v"(qrow), "n"(kk * 32) : "memory");
     if constexpr (IDX) wait_vmcnt<0>();        // the first two stages' indices (and the queries) are in
+    // (indexed: from here on every stage asks for one set of indices and issues one set of copies, in that order)
 #pragma unroll
     for (int p = 0; p < PF; ++p) {
         if (p < tA) issue(p);
         if (IDX && p + 2 <= PF) ask(p + 2);
     }
-    // (indexed: from here on every stage asks for one set of indices and issues one set of copies, in that order)
-    if (tA >= PF) wait_vmcnt<PF * NC + (PF - 1) * NI>();             // the queries are in, the stages may be in flight
+    // The queries are in.  With one stage ahead the first stage waits for its copies next anyway, so everything is
+    // waited for, on every path; with more stages ahead the later ones stay in flight.
+    if (PF > 1 && tA >= PF) wait_vmcnt<PF * NC + (PF - 1) * NI>();
     else wait_vmcnt<0>();
     bf16x8_t qf[NK];
 #pragma unroll
@@ -375,15 +379,19 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     };
 
     // One stage: `bi` is its buffer (a constant at every call, so LDS offsets are immediates)
-    auto stage = [&](int sidx, int bi) {
+    auto stage = [&](int sidx, int bi, auto tail) {   // tail: the stage after the last whole round, nothing follows it
         // this wave's copies of the stage have landed (those of later stages may still be in flight) ...
         // (younger than them: the next stage's copies and, indexed, the index loads behind which they were issued)
         if (PF == 2 && sidx + 1 < tA) wait_vmcnt<NC + NI>();
         else wait_vmcnt<0>();
         // ... and so have everybody's; all waves are through with the buffer that is refilled next
         lds_only_barrier();
-        if constexpr (IDX) ask(bi);            // rows of stage sidx + PF + 1; its set last served stage sidx
-        if (sidx + PF < tA) {
+        // rows of stage sidx + PF + 1; its set last served stage sidx.  Asked for only if that stage exists: a load
+        // whose result nobody reads has a destination the compiler counts as free while the load is still in flight.
+        if constexpr (IDX && !decltype(tail)::value) {
+            if (sidx + PF + 1 < tA) ask(bi);
+        }
+        if (!decltype(tail)::value && sidx + PF < tA) {
             // indexed: the set of stage sidx + PF, asked for one stage ago, has only the previous stage's copies and
             // the loads just issued behind it
             if constexpr (IDX) wait_vmcnt<NC + NI>();
@@ -402,11 +410,15 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
             for (int i = 0; i < NA; ++i) pv_mfma(i, 1);
         }
     };
-    for (int s0 = 0; s0 < tA; s0 += NBUF) {
+    // Whole rounds of the buffer ring first, every stage of a round unconditionally, then the ragged rest: inside the
+    // loop each stage's wait is then passed on every way round, whatever the trip count.
+    int s0 = 0;
+    for (; s0 + NBUF <= tA; s0 += NBUF) {
 #pragma unroll
-        for (int bi = 0; bi < NBUF; ++bi)
-            if (s0 + bi < tA) stage(s0 + bi, bi);
+        for (int bi = 0; bi < NBUF; ++bi) stage(s0 + bi, bi, std::false_type{});
     }
+    static_assert(NBUF == 2, "the ragged rest is taken to be one stage, the last");
+    if (s0 < tA) stage(s0, 0, std::true_type{});
     // The last stages have asked for indices that no copy will use.  Those loads are invisible to the compiler, which
     // is free to give their destination registers to something else from here on: they must have landed first.
     if constexpr (IDX) wait_vmcnt<0>();
