@@ -38,13 +38,6 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 namespace {
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
 // Result layout of v_mfma_f32_32x32x*: lane l, register r hold element
 // (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
 __device__ __forceinline__ int mfma_row(int r, int hb) { return 8 * (r >> 2) + 4 * hb + (r & 3); }

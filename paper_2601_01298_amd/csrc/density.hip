@@ -98,13 +98,6 @@ struct F32Tr {
     static __device__ __forceinline__ double widen(Elem e) { return (double)e; }
 };
 
-__device__ __forceinline__ uint32_t bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
 // ------------------------------------------------------------------------------------------
 // Prepass.
 //   density_stats   (bf16)  per head, coordinate and chunk of rows: minimum, maximum, smallest non-zero magnitude

@@ -25,12 +25,6 @@ rope_table(const int32_t *__restrict__ pos, int m, int d, double base, float2 *_
     tab[g] = make_float2((float)cs, (float)sn);
 }
 
-__device__ __forceinline__ uint32_t bf16_rne(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;      // finite inputs
-}
-
 template <bool BF16>
 __global__ void __launch_bounds__(256)
 inject_rows(void *__restrict__ Kc, void *__restrict__ Vc, const void *__restrict__ Knew,

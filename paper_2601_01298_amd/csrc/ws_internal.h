@@ -10,6 +10,13 @@ constexpr int kWave = 64;
 
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
+// fp32 -> bf16 bit pattern, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_rne(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 // Sum over aligned groups of LPR consecutive lanes (LPR a power of two); every lane of a group ends up with
 // the group's sum.  Inside a row of 16 lanes the partners are reached by DPP operands of the add itself
 // (swap in pairs, swap pairs in quads, mirror 8, mirror 16: the same partners as xor 1, 2, 4, 8, so the
