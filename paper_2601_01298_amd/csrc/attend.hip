@@ -412,8 +412,9 @@ attend_bf16(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Ks, con
     }
     static_assert(NBUF == 2, "the ragged rest is taken to be one stage, the last");
     if (s0 < tA) stage(s0, 0, std::true_type{});
-    // The last stages have asked for indices that no copy will use.  Those loads are invisible to the compiler, which
-    // is free to give their destination registers to something else from here on: they must have landed first.
+    // The index loads are invisible to the compiler, which is free to give their destination registers to something
+    // else from here on.  Every set asked for has been waited for by the stage that used it; this wait states it for
+    // the whole loop, whatever the trip count, so that nothing of it is in flight when the registers change hands.
     if constexpr (IDX) wait_vmcnt<0>();
 
     // ---- merge the two halves of the landmark range: half 1 hands its state to half 0 through LDS
