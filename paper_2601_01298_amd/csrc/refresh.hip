@@ -5,8 +5,10 @@
 // one pass over K -- O(L m d), HBM-bound for small m -- instead of the O(L^2 d) sweep.
 //   append_sweep   a workgroup per 2048-key tile of one head; the m new rows sit in LDS as fp32;
 //                  a lane group per key row (16-byte loads, 4 rows in flight), squared distances by
-//                  direct differences in fp32, exp2; old keys get their refreshed density at once,
-//                  column sums leave as one partial per (tile, new row);
+//                  direct differences in fp32, exp2; what the new rows add to each old key waits in LDS
+//                  and the tile's refreshed densities are written in one coalesced pass at the end (a
+//                  4-byte load and store per row group inside the loop cost 13 %: each iteration then
+//                  waits on memory twice); column sums leave as one partial per (tile, new row);
 //   append_finish  adds the partials of each new row in tile order (deterministic) and writes the
 //                  m new densities.
 #include "ws_internal.h"
@@ -20,8 +22,10 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kAppTile = 2048;
 constexpr int kAppMaxM = 32;
 
+constexpr int kAppChunk = 768;               // heads per launch: their scales travel as a kernel argument (3 KB)
+
 struct AppScale {
-    float s[256];     // 0.5 * log2(e) / sigma^2 per head of the chunk
+    float s[kAppChunk];     // 0.5 * log2(e) / sigma^2 per head of the chunk
 };
 
 template <bool BF16>
@@ -52,6 +56,7 @@ append_sweep(const void *__restrict__ Kv, const float *__restrict__ rho_old, flo
     constexpr int UN = 4;
     __shared__ float nr[kAppMaxM][D];        // the new rows, widened
     __shared__ float cs[kAppMaxM][RP];       // column sums, one slot per row group
+    __shared__ float added[kAppTile];        // what the new rows add to each old key of the tile
 
     const int h = head0 + blockIdx.y, blk = blockIdx.x;
     const int tid = threadIdx.x, sub = tid % LPR, rsub = tid / LPR;
@@ -107,13 +112,14 @@ append_sweep(const void *__restrict__ Kv, const float *__restrict__ rho_old, flo
 #pragma unroll
             for (int u = 0; u < UN; ++u) {
                 const int i = r0 + u * RP + rsub;
-                if (i < hi && i < Lold)
-                    rho_new[(size_t)h * L + i] =
-                        (rho_old[(size_t)h * Lold + i] * (float)Lold + add[u]) / (float)L;
+                if (i < hi) added[i - lo] = add[u];
             }
         }
     }
     __syncthreads();
+    // the old keys' refreshed densities, a whole tile at a time: consecutive threads, consecutive keys
+    for (int i = lo + tid; i < min(hi, Lold); i += 256)
+        rho_new[(size_t)h * L + i] = (rho_old[(size_t)h * Lold + i] * (float)Lold + added[i - lo]) / (float)L;
     if (tid < m) {
         float t = 0.0f;
         for (int g = 0; g < RP; ++g) t += cs[tid][g];
@@ -147,7 +153,7 @@ int append_max_rows() { return kAppMaxM; }
 size_t append_workspace_bytes(int H, int L)
 {
     const int nblk = (L + kAppTile - 1) / kAppTile;
-    const int nh = H < 256 ? H : 256;
+    const int nh = H < kAppChunk ? H : kAppChunk;
     return round_up((size_t)nh * nblk * kAppMaxM * sizeof(float), 256);
 }
 
@@ -156,10 +162,10 @@ hipError_t launch_density_append(const void *K, bool bf16, int H, int L, int d, 
 {
     const int nblk = (L + kAppTile - 1) / kAppTile;
     float *colpart = reinterpret_cast<float *>(ws);
-    for (int h0 = 0; h0 < H; h0 += 256) {
-        const int nh = (H - h0 < 256) ? H - h0 : 256;
+    for (int h0 = 0; h0 < H; h0 += kAppChunk) {
+        const int nh = (H - h0 < kAppChunk) ? H - h0 : kAppChunk;
         AppScale sc;
-        for (int i = 0; i < 256; ++i) {
+        for (int i = 0; i < kAppChunk; ++i) {
             const double sg = (i < nh) ? (double)sigma_host[h0 + i] : 1.0;
             sc.s[i] = (float)(0.5 * 1.4426950408889634 / (sg * sg));
         }
