@@ -5,8 +5,8 @@
 // the O(L^2 d) of the kernel density it can stand in for.  Two kernels:
 //   mass_logits   one workgroup per (2048-token tile, KV head): 16-byte loads of the key rows, a
 //                 lane group per row, the dot products of all query heads that share the KV head
-//                 from one read; writes the logits (log2 units) and a (max, sum of exp2) pair per
-//                 (query head, tile);
+//                 from one read; writes the logits (log2 units; staged in LDS, one coalesced pass per
+//                 tile) and a (max, sum of exp2) pair per (query head, tile);
 //   mass_combine  folds the pairs of a layer's heads into (max, 1/sum) per head, then per token adds
 //                 the normalised exponentials over the heads and writes the result to every KV head
 //                 of the layer (as A, or as 1/A when it is to serve as the density).
@@ -71,6 +71,11 @@ mass_logits(const void *__restrict__ Kv, const void *__restrict__ Qv, float *__r
     constexpr int RP = 256 / LPR;         // rows per pass of the workgroup
     constexpr int UN = 4;                 // rows in flight per lane group
     __shared__ float wm[4][MAXG], wsum[4][MAXG];
+    // The logits of the tile wait in LDS and leave in one coalesced pass at the end: a 4-byte store per row group
+    // inside the streaming loop costs a memory transaction per 32 bytes.  (Eight query heads per KV head would need
+    // 64 KB: those keep the direct stores.)
+    constexpr bool STAGE = MAXG <= 4;
+    __shared__ float zt[STAGE ? MAXG : 1][STAGE ? kMassTile : 1];
 
     const int kvh = blockIdx.y, blk = blockIdx.x;
     const int tid = threadIdx.x, sub = tid % LPR, rsub = tid / LPR;
@@ -114,7 +119,10 @@ mass_logits(const void *__restrict__ Kv, const void *__restrict__ Qv, float *__r
                     acc = lane_group_sum<LPR>(acc);
                     const float zz = acc * scale2;
                     if (i < hi) {
-                        if (sub == 0) z[(size_t)(kvh * g + j) * L + i] = zz;
+                        if (sub == 0) {
+                            if constexpr (STAGE) zt[j][i - lo] = zz;
+                            else z[(size_t)(kvh * g + j) * L + i] = zz;
+                        }
                         const float mn = fmaxf(m[j], zz);
                         s[j] = s[j] * __builtin_amdgcn_exp2f(m[j] - mn) + __builtin_amdgcn_exp2f(zz - mn);
                         m[j] = mn;
@@ -142,6 +150,12 @@ mass_logits(const void *__restrict__ Kv, const void *__restrict__ Qv, float *__r
         }
     }
     __syncthreads();
+    if constexpr (STAGE) {
+#pragma unroll
+        for (int j = 0; j < MAXG; ++j)
+            if (j < g)
+                for (int i = lo + tid; i < hi; i += 256) z[(size_t)(kvh * g + j) * L + i] = zt[j][i - lo];
+    }
     if (tid < g) {
         float mm = wm[0][tid], ss = wsum[0][tid];
         for (int w = 1; w < 4; ++w) merge(mm, ss, wm[w][tid], wsum[w][tid]);
