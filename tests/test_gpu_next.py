@@ -106,6 +106,25 @@ def test_density_append(ws, oracle, cfg, H, L, m):
     assert worst <= RHO_TOL[w.dtype]
 
 
+def test_density_append_many_heads(ws, oracle):
+    """More heads than one launch of the sweep takes (their scales travel as a kernel argument, 768 at a time):
+    heads on both sides of the seam against the oracle, every head against the full density of the library."""
+    import torch
+    H, L, m = 771, 300, 2
+    w = variant(2, H=H, Hq=H, L=L)
+    K = np.stack([syn.cloud(w, h, syn.TENSOR_K) for h in range(H)])
+    sigma = [float(syn.bandwidth(K[h])) for h in range(H)]
+    Kd = to_device(K, w.dtype)
+    rho_old = ws.ws_synapse_density(Kd[:, :L - m].contiguous(), sigma)
+    rho_new = ws.ws_synapse_density_append(Kd, m, sigma, rho_old)
+    full = ws.ws_synapse_density(Kd, sigma)
+    assert float((rho_new / full - 1).abs().max()) <= 2 * RHO_TOL[w.dtype]
+    rho_new = rho_new.cpu().numpy()
+    worst = max(np.abs(rho_new[h] / oracle.density(K[h], sigma[h]) - 1).max() for h in (0, 1, 767, 768, 769, 770))
+    print(f"density append across the launch seam (H={H}): max rel err {worst:.2e}")
+    assert worst <= RHO_TOL[w.dtype]
+
+
 def test_density_append_repeated_steps(ws, oracle):
     """Forty decode steps of one row each, chained, against the oracle's density of the final cloud."""
     w = variant(2, H=2, Hq=2, L=1500)
