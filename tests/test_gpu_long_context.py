@@ -100,3 +100,11 @@ def test_long_context_gqa_full_size(oracle, say):
               f"forks {forks} (streaming kernel: {forks_s}); attention rel err (N={w.N}, {g} query heads) {aerr:.2e}")
         assert err <= 5e-5 and aerr <= 2e-3
     say(f"long-context config: {ties_total} near-tie steps survived, {forks_total} near-tie forks on {w.H} heads")
+
+    # ---- where the forks come from: the same comparison with the oracle fed the library's own density (fp32, widened
+    # exactly) on the first and the last head.  What is left then is the selection's arithmetic alone.
+    for h in (0, w.H - 1):
+        rho64 = rho_h[h].astype(np.float64)
+        ref, _, gap = oracle.select(Kh[h], rho64, w.k, w.alpha)
+        forks = check_indices(oracle, Kh[h], rho64, w.k, w.alpha, idx_h[h], ref)
+        say(f"head {h}, selection on the library's density: {forks} forks ({int((gap < TIE_TOL).sum())} oracle steps under tie tolerance)")
