@@ -260,3 +260,43 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+C_CONSUMER = r"""
+#include <stdio.h>
+#include <string.h>
+#include "ws_synapse.h"
+int main(void)
+{
+    /* a consumer written in C: only calls that need no device */
+    size_t n = ws_synapse_workspace_bytes(WS_OP_SELECT, WS_BF16, 16, 4096, 64, 82, 100, 16);
+    if (n == 0) return 1;
+    if (strcmp(ws_status_string(WS_OK), "ok") != 0) return 2;
+    /* arguments are checked on the host before anything is launched */
+    if (ws_synapse_gather(NULL, NULL, WS_BF16, 1, 8, 64, NULL, 4, NULL, NULL, NULL) != WS_ERR_INVALID_ARG) return 3;
+    printf("%zu\n", n);
+    return 0;
+}
+"""
+
+
+@pytest.mark.parametrize("compiler,std,suffix", [("gcc", "-std=c99", ".c"), ("g++", "-std=c++11", ".cpp")])
+def test_header_serves_a_plain_c_and_a_cxx_consumer(lib, tmp_path, compiler, std, suffix):
+    """The header compiles as strict C99 and as C++ without the HIP headers, and a program built from it links
+    against the library and runs on a host without a GPU."""
+    import shutil
+    import subprocess
+    from paper_2601_01298_amd import binding
+    if shutil.which(compiler) is None:
+        pytest.skip(f"no {compiler}")
+    src = tmp_path / ("consumer" + suffix)
+    src.write_text(C_CONSUMER)
+    exe = tmp_path / "consumer"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    cmd = [compiler, std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.dirname(HEADER), str(src), "-o", str(exe),
+           "-L", libdir, "-l:" + os.path.basename(binding.LIB_PATH), "-Wl,-rpath," + libdir]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr[-500:])
+    assert int(r.stdout.strip()) == binding.ws_synapse_workspace_bytes(binding.WS_OP_SELECT, binding.WS_BF16, 16, 4096, 64, k=82, N=100, Hq=16)
