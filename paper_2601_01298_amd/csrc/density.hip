@@ -300,7 +300,10 @@ density_prep(const typename TR::Elem *__restrict__ K, PrepWs w, int L, int Lpad)
     }
     if (j < Lpad) {
         w.ext[(size_t)h * Lpad + j] = rec;
-        if (w.acc) w.acc[(size_t)h * Lpad + j] = 0ull;
+        // the symmetric sweep's cell of a key starts at its self term, exactly 1 (in 32.32 fixed point): kept out of
+        // the fp32 row accumulators, where a 1 would swallow the many kernel values below its half ulp that make
+        // up the rest of an isolated key's sum
+        if (w.acc) w.acc[(size_t)h * Lpad + j] = (j < L) ? (1ull << 32) : 0ull;
     }
     // sum of the block's squared norms, in a fixed order
     part[threadIdx.x] = n;
@@ -507,7 +510,7 @@ __device__ __forceinline__ void sym_tile(const bf16x8_t (&a)[RTW][D / 16 + 1], c
         if (DIAG && rt == diag_rt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                if (8 * (r >> 2) + 4 * hb + (r & 3) == n) cur[r] = 0.0f;   // a key's distance to itself
+                if (8 * (r >> 2) + 4 * hb + (r & 3) == n) cur[r] = -1e30f;   // the self term is in the cell already
         }
         if (rt + 1 < RTW) {
 #pragma unroll
